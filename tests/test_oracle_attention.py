@@ -1,0 +1,192 @@
+"""Pins for the oracle's DAG-masked attention (Sections 4.1 / 5.4): library SDPA in fp64, causal special
+case, closed forms and invariances."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_16207_amd.workload import (VerifyConfig, make_workload, random_dag, bf16_bits_to_f32)
+from helpers import mask_to_bool, chain_dag
+
+
+def as_f64(x):
+    return (bf16_bits_to_f32(x) if x.dtype == np.uint16 else x).astype(np.float64)
+
+
+def sdpa_reference(w, mask):
+    """Dense masked scaled-dot-product attention per sequence with torch's CPU routine in fp64."""
+    cfg = w.cfg
+    G = cfg.num_q_heads // cfg.num_kv_heads
+    outs = []
+    for b in range(cfg.batch):
+        n0, n1 = int(w.node_offsets[b]), int(w.node_offsets[b + 1])
+        n, P = n1 - n0, int(w.prefix_lens[b])
+        r0 = int(w.kv_offsets[b])
+        q = torch.from_numpy(as_f64(w.q[n0:n1])).permute(1, 0, 2)                       # [Hq, n, D]
+        k = torch.from_numpy(as_f64(w.k[r0:r0 + P + n])).permute(1, 0, 2).repeat_interleave(G, dim=0)
+        v = torch.from_numpy(as_f64(w.v[r0:r0 + P + n])).permute(1, 0, 2).repeat_interleave(G, dim=0)
+        allow = np.concatenate([np.ones((n, P), dtype=bool), mask_to_bool(mask[n0:n1], n)], axis=1)
+        o = torch.nn.functional.scaled_dot_product_attention(
+            q[None], k[None], v[None], attn_mask=torch.from_numpy(allow)[None, None], scale=w.softmax_scale)[0]
+        outs.append(o.permute(1, 0, 2).numpy())
+    return np.concatenate(outs, axis=0)
+
+
+SMALL = VerifyConfig("t", 3, 4, 2, 16, 5, 40, 5, 4, 3, 50, 0.7, "f32")
+SMALL_BF16 = VerifyConfig("t", 2, 6, 3, 32, 0, 70, 9, 8, 2, 50, 0.7, "bf16")
+
+
+@pytest.mark.parametrize("cfg", [SMALL, SMALL_BF16, 1])
+def test_equals_library_sdpa_with_expanded_mask(ref, cfg):
+    w = make_workload(cfg, seed=7) if not isinstance(cfg, int) else make_workload(cfg)
+    mask, _ = ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    out = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale)
+    np.testing.assert_allclose(out, sdpa_reference(w, mask), rtol=0, atol=1e-12)
+
+
+def test_chain_is_causal_attention(ref):
+    """A chain-shaped graph (plain sequence-structured drafting, Section 3) must reduce to ordinary causal
+    attention over [prefix ; draft], read off at the last n positions."""
+    rng = np.random.default_rng(3)
+    P, n, H, D = 37, 21, 3, 16
+    q = rng.standard_normal((n, H, D)).astype(np.float32)
+    k = rng.standard_normal((P + n, H, D)).astype(np.float32)
+    v = rng.standard_normal((P + n, H, D)).astype(np.float32)
+    off, par = chain_dag(n)
+    mask, _ = ref.build_mask([0, n], off, par)
+    out = ref.dag_attention(q, k, v, [0], [P], [0, n], mask, 0.25)
+    # causal attention over the full sequence with zero-padded queries for the prefix positions
+    qf = torch.zeros(H, P + n, D, dtype=torch.float64)
+    qf[:, P:] = torch.from_numpy(q.astype(np.float64)).permute(1, 0, 2)
+    kf = torch.from_numpy(k.astype(np.float64)).permute(1, 0, 2)
+    vf = torch.from_numpy(v.astype(np.float64)).permute(1, 0, 2)
+    o = torch.nn.functional.scaled_dot_product_attention(qf[None], kf[None], vf[None], is_causal=True, scale=0.25)[0]
+    np.testing.assert_allclose(out, o[:, P:].permute(1, 0, 2).numpy(), rtol=0, atol=1e-12)
+
+
+def test_lse_matches_logsumexp(ref):
+    w = make_workload(SMALL, seed=11)
+    mask, _ = ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    _, lse = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask,
+                               w.softmax_scale, return_lse=True)
+    b, i, h = 1, 7, 3
+    t = int(w.node_offsets[b]) + i
+    P, r0 = int(w.prefix_lens[b]), int(w.kv_offsets[b])
+    vis = mask_to_bool(mask[t:t + 1], w.cfg.nodes)[0]
+    rows = list(range(r0, r0 + P)) + [r0 + P + j for j in np.nonzero(vis)[0]]
+    s = (w.k[rows, h // 2].astype(np.float64) @ w.q[t, h].astype(np.float64)) * w.softmax_scale
+    assert abs(lse[t, h] - torch.logsumexp(torch.from_numpy(s), 0).item()) < 1e-12
+
+
+def test_constant_values_give_constant_output(ref):
+    w = make_workload(SMALL, seed=5)
+    mask, _ = ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    v = np.ones_like(w.v)
+    out = ref.dag_attention(w.q, w.k, v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale)
+    np.testing.assert_allclose(out, 1.0, rtol=0, atol=1e-14)
+
+
+def test_single_node_is_decode_attention(ref):
+    rng = np.random.default_rng(8)
+    P, H, D = 50, 2, 8
+    q = rng.standard_normal((1, H, D)).astype(np.float32)
+    k = rng.standard_normal((P + 1, H, D)).astype(np.float32)
+    v = rng.standard_normal((P + 1, H, D)).astype(np.float32)
+    out = ref.dag_attention(q, k, v, [0], [P], [0, 1], np.array([[1]], dtype=np.uint64), 0.3)
+    for h in range(H):
+        s = k[:, h].astype(np.float64) @ q[0, h].astype(np.float64) * 0.3
+        p = torch.softmax(torch.from_numpy(s), 0).numpy()
+        np.testing.assert_allclose(out[0, h], p @ v[:, h].astype(np.float64), rtol=0, atol=1e-13)
+
+
+def test_gqa_equals_mha_with_repeated_kv(ref):
+    w = make_workload(SMALL, seed=13)
+    mask, _ = ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    out = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale)
+    G = w.cfg.num_q_heads // w.cfg.num_kv_heads
+    out2 = ref.dag_attention(w.q, np.repeat(w.k, G, axis=1), np.repeat(w.v, G, axis=1), w.kv_offsets,
+                             w.prefix_lens, w.node_offsets, mask, w.softmax_scale)
+    assert np.array_equal(out, out2)
+
+
+def test_relabelling_permutes_rows_only(ref):
+    """Another topological order of the same graph permutes the output rows and changes nothing else."""
+    rng = np.random.default_rng(21)
+    n, P, H, D = 24, 9, 2, 8
+    off, par = random_dag(rng, n, 3)
+    q = rng.standard_normal((n, H, D)).astype(np.float32)
+    k = rng.standard_normal((P + n, H, D)).astype(np.float32)
+    v = rng.standard_normal((P + n, H, D)).astype(np.float32)
+    mask, _ = ref.build_mask([0, n], off, par)
+    out = ref.dag_attention(q, k, v, [0], [P], [0, n], mask, 0.35)
+    # a different topological order: repeatedly pick a random node all of whose parents are placed
+    placed, order = set(), []
+    while len(order) < n:
+        ready = [i for i in range(n) if i not in placed and all(p < 0 or p in placed for p in par[off[i]:off[i + 1]])]
+        pick = int(rng.choice(ready))
+        placed.add(pick)
+        order.append(pick)
+    new_id = {old: new for new, old in enumerate(order)}
+    off2, par2 = [0], []
+    for old in order:
+        par2 += sorted(-1 if p < 0 else new_id[int(p)] for p in par[off[old]:off[old + 1]])
+        off2.append(len(par2))
+    perm = np.asarray(order)
+    k2 = np.concatenate([k[:P], k[P:][perm]])
+    v2 = np.concatenate([v[:P], v[P:][perm]])
+    mask2, flag = ref.build_mask([0, n], off2, par2)
+    assert flag == 0
+    out2 = ref.dag_attention(q[perm], k2, v2, [0], [P], [0, n], mask2, 0.35)
+    np.testing.assert_allclose(out2, out[perm], rtol=0, atol=1e-13)
+
+
+def test_edge_to_existing_ancestor_changes_nothing(ref):
+    rng = np.random.default_rng(4)
+    n, P, H, D = 12, 4, 1, 8
+    off, par = chain_dag(n)
+    q = rng.standard_normal((n, H, D)).astype(np.float32)
+    k = rng.standard_normal((P + n, H, D)).astype(np.float32)
+    v = rng.standard_normal((P + n, H, D)).astype(np.float32)
+    mask, _ = ref.build_mask([0, n], off, par)
+    # node 9 additionally names node 2 (already its ancestor)
+    par2 = np.concatenate([par[:10], [2], par[10:]]).astype(np.int32)
+    par2[9], par2[10] = 2, 8
+    off2 = off.copy()
+    off2[10:] += 1
+    mask2, _ = ref.build_mask([0, n], off2, par2)
+    assert np.array_equal(mask, mask2)
+    assert np.array_equal(ref.dag_attention(q, k, v, [0], [P], [0, n], mask, 0.3),
+                          ref.dag_attention(q, k, v, [0], [P], [0, n], mask2, 0.3))
+
+
+def test_sequences_are_independent_and_rows_subset(ref):
+    w = make_workload(SMALL, seed=17)
+    mask, _ = ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    out = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale)
+    b = 1
+    n0, n1 = int(w.node_offsets[b]), int(w.node_offsets[b + 1])
+    r0, P = int(w.kv_offsets[b]), int(w.prefix_lens[b])
+    solo = ref.dag_attention(w.q[n0:n1], w.k[r0:r0 + P + n1 - n0], w.v[r0:r0 + P + n1 - n0], [0], [P],
+                             [0, n1 - n0], mask[n0:n1], w.softmax_scale)
+    assert np.array_equal(solo, out[n0:n1])
+    rb, ri, rh = [0, 2, 1], [3, 19, 0], [1, 3, 0]
+    sub = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale,
+                            rows=(rb, ri, rh))
+    for r in range(3):
+        assert np.array_equal(sub[r], out[int(w.node_offsets[rb[r]]) + ri[r], rh[r]])
+
+
+def test_mask_bit_decides_visibility(ref):
+    """Making one draft key's value huge changes exactly the rows whose mask has that bit."""
+    w = make_workload(SMALL, seed=23)
+    mask, _ = ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    base = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale)
+    b, j = 2, 6
+    v = w.v.copy()
+    v[int(w.kv_offsets[b]) + int(w.prefix_lens[b]) + j] += 1000.0
+    out = ref.dag_attention(w.q, w.k, v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale)
+    n0 = int(w.node_offsets[b])
+    vis = mask_to_bool(mask[n0:n0 + w.cfg.nodes], w.cfg.nodes)
+    changed = np.abs(out - base).max(axis=(1, 2)) > 0
+    expect = np.zeros(w.total_nodes, dtype=bool)
+    expect[n0:n0 + w.cfg.nodes] = vis[:, j]
+    assert np.array_equal(changed, expect)
