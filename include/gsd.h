@@ -1,0 +1,167 @@
+/*
+ * gsd.h -- C ABI of the MI355X (gfx950) verification hot path of Graph-structured Speculative Decoding.
+ *
+ * One verifier pass over the flattened token graph (paper Sections 4.1, 5.3, 5.4) and the deterministic
+ * acceptance step (Section 3):
+ *
+ *   gsd_build_mask            token graph (DAG) -> per-node visibility bitmask (ancestor closure)
+ *   gsd_dag_attention         masked attention of every packed draft node over [context ; visible nodes]
+ *   gsd_node_argmax           the verifier's own next token after every node (row argmax of the logits)
+ *   gsd_accept_longest_path   longest root path on which every drafted token equals the verifier's choice
+ *
+ * Conventions common to all calls
+ *   - Every data pointer is a DEVICE pointer owned by the caller; scalars and the descriptor struct are host
+ *     values.  The library allocates nothing, frees nothing and keeps no state between calls.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default stream) and the call
+ *     returns without synchronising.  Outputs are deterministic run to run (bit-identical).
+ *   - Return value: GSD_OK or a GSD_ERR_* code.  Host-checkable mistakes (null pointer, non-positive size,
+ *     unsupported head_dim, head counts that do not divide, words_per_row or workspace too small) are
+ *     reported before anything is launched and leave all outputs untouched; gsd_last_error() then holds a
+ *     detail string for the calling thread.  Mistakes only the device can see (a parent id that is not an
+ *     earlier node) are reported through `dag_error_flag`.
+ *   - Packed nodes: sequence b owns packed rows node_offsets[b] .. node_offsets[b+1]-1, listed in a
+ *     topological order of its graph; parent ids are sequence-local, -1 names the root (the context at the
+ *     start of drafting, Section 4).
+ */
+#ifndef GSD_H
+#define GSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    GSD_OK = 0,
+    GSD_ERR_INVALID_ARG = 1,
+    GSD_ERR_NOT_TOPOLOGICAL = 2, /* reserved for callers that read dag_error_flag back */
+    GSD_ERR_UNSUPPORTED = 3,
+    GSD_ERR_WORKSPACE = 4,
+    GSD_ERR_HIP = 5
+};
+
+enum { GSD_F32 = 0, GSD_BF16 = 1 };
+
+/* Limits of this build. */
+#define GSD_MAX_NODES_PER_SEQ 512 /* nodes of one sequence (mask builder and acceptance keep a sequence in LDS) */
+
+/* Static strings; never NULL. */
+const char *gsd_status_string(int status);
+/* Detail of the last error returned on this thread ("" if none). */
+const char *gsd_last_error(void);
+/* Library version string, e.g. "gsd-gfx950 0.1". */
+const char *gsd_version(void);
+
+/*
+ * Visibility mask (Section 4.1: a flattened token attends only to its ancestors; Section 5.3: the token graph
+ * is a DAG, so "ancestors" is the closure over ALL parent edges).  For every packed node t = node_offsets[b]+i
+ *     mask[t][j/64] bit (j%64, LSB first) = 1  iff  j == i or node j of sequence b is an ancestor of node i.
+ * The row is fully overwritten (bits at and beyond the sequence's node count are 0).  The root is not a bit:
+ * the context is visible to every node.
+ *
+ *   batch            B >= 1
+ *   max_nodes        upper bound on the nodes of any one sequence, 1..GSD_MAX_NODES_PER_SEQ
+ *   node_offsets     [B+1] int32
+ *   parent_offsets   [T+1] int32, CSR over packed nodes (T = node_offsets[B])
+ *   parent_idx       [E]   int32, sequence-local parent id (< the child's id) or -1 for the root
+ *   mask             [T][words_per_row] uint64, words_per_row >= ceil(max_nodes/64)
+ *   dag_error_flag   [1] int32 or NULL; set to 1 (never cleared) if some parent id is >= its child or < -1;
+ *                    such an edge is ignored.  Clear it before the call if you read it afterwards.
+ */
+int gsd_build_mask(int32_t batch, int32_t max_nodes, int32_t words_per_row, const int32_t *node_offsets,
+                   const int32_t *parent_offsets, const int32_t *parent_idx, uint64_t *mask,
+                   int32_t *dag_error_flag, void *hip_stream);
+
+/*
+ * DAG-masked attention (Sections 4.1 and 5.4: the verifier scores all hypotheses in one pass over the
+ * flattened graph).  For packed node t of sequence b and query head h (KV head h / (Hq/Hkv)):
+ *     O[t][h] = softmax_j( scale * <Q[t][h], K_j> ) . V_j     over j in  prefix rows 0..P_b-1 of sequence b
+ *                                                              and draft rows whose bit is set in mask[t]
+ * Sequence b's K/V rows are contiguous: row kv_offsets[b] + j for prefix position j < P_b, then row
+ * kv_offsets[b] + P_b + i for draft node i.  Element (row, kv_head, d) lives at
+ * row*kv_token_stride + kv_head*kv_head_stride + d (strides in elements; d is contiguous).  Q and O element
+ * (t, h, d) lives at t*token_stride + h*head_stride + d.  Rows must be 16-byte aligned (pointers and strides
+ * multiples of 8 elements for bf16, 4 for f32).
+ *
+ * dtype GSD_BF16: Q/K/V/O are bf16, both contractions run on the matrix cores with fp32 accumulation, softmax
+ * in fp32, O rounded to nearest-even.  dtype GSD_F32: everything fp32.  head_dim must be 64 or 128.
+ * lse (optional, [T][Hq] fp32): natural-log sum of exp of the scaled scores over the visible keys.
+ *
+ * Small problems are split along the KV prefix across work-groups and merged by a second kernel in a fixed
+ * order; the partial results live in `workspace` (gsd_dag_attention_workspace() bytes, 0 if unsplit).
+ */
+typedef struct gsd_attn_desc {
+    int32_t batch;         /* B */
+    int32_t total_nodes;   /* T = node_offsets[B] (host copy) */
+    int32_t max_nodes;     /* upper bound on nodes per sequence (sizes the grid) */
+    int32_t max_prefix;    /* upper bound on prefix_lens[b] (sizes the KV split) */
+    int32_t num_q_heads;   /* Hq */
+    int32_t num_kv_heads;  /* Hkv, divides Hq */
+    int32_t head_dim;      /* D: 64 or 128 */
+    int32_t dtype;         /* GSD_F32 or GSD_BF16 */
+    int32_t words_per_row; /* uint64 words per mask row, >= ceil(max_nodes/64) */
+    int32_t num_splits;    /* KV splits: 0 = let the library choose, >= 1 = forced */
+    float softmax_scale;   /* e.g. 1/sqrt(D) */
+    int32_t reserved;
+    const void *q;         /* [T][Hq][D] via strides */
+    void *o;               /* same shape and dtype as q */
+    float *lse;            /* [T][Hq] contiguous, or NULL */
+    const void *k;
+    const void *v;
+    const int64_t *kv_offsets;   /* [B] */
+    const int32_t *prefix_lens;  /* [B] */
+    const int32_t *node_offsets; /* [B+1] */
+    const uint64_t *mask;        /* [T][words_per_row] from gsd_build_mask */
+    int64_t q_token_stride, q_head_stride;
+    int64_t o_token_stride, o_head_stride;
+    int64_t kv_token_stride, kv_head_stride;
+    void *workspace;             /* device scratch for split partials, may be NULL when 0 bytes are needed */
+    size_t workspace_bytes;
+} gsd_attn_desc;
+
+/* Bytes of workspace gsd_dag_attention needs for this descriptor (0 when it will not split).  Returns
+ * (size_t)-1 if the descriptor is invalid (see gsd_last_error()).  Touches no device memory. */
+size_t gsd_dag_attention_workspace(const gsd_attn_desc *desc);
+/* Number of KV splits the library will use for this descriptor (>= 1), or -1 if invalid. */
+int gsd_dag_attention_splits(const gsd_attn_desc *desc);
+int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream);
+
+/*
+ * Deterministic verification, part 1 (Section 3: a drafted token is accepted only if the LLM would generate
+ * the same): pred[r] = the lowest index holding the largest value of row r of the logits.  NaN never wins; a
+ * row of only NaN gives 0.  logits element (r, x) lives at r*row_stride + x (elements).
+ *   rows >= 1, vocab >= 1, dtype GSD_F32 or GSD_BF16, pred [rows] int32.
+ */
+int gsd_node_argmax(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
+                    int32_t *pred, void *hip_stream);
+
+/*
+ * Deterministic verification, part 2 (Sections 3 and 4.1): an edge p -> i is accepted iff tokens[i] equals
+ * the LLM's choice after p (pred[p]; root_pred[b] when p is the root).  A root path is accepted iff all its
+ * edges are: the first mismatch discards everything after it.  Per sequence the longest accepted root path
+ * is returned; among equally long ones the end node with the smallest id wins and, walking back, the
+ * smallest-id parent that continues a path of full length (the root counts as smallest).
+ *
+ *   total_nodes  T = node_offsets[B] (host copy; sizes the argmax launch)
+ *   tokens       [T] int32 drafted token of every packed node
+ *   logits       [T][vocab] or NULL.  When given, pred is first filled by gsd_node_argmax on the same stream.
+ *   pred         [T] int32: output when logits != NULL, input otherwise
+ *   root_pred    [B] int32: the LLM's choice right after the context
+ *   accept_len   [B] int32: number of accepted draft nodes (0 if none)
+ *   accept_path  [B][max_nodes] int32: sequence-local node ids from the root outwards, -1 padded
+ *   bonus_token  [B] int32: the LLM's choice after the last accepted node (root_pred[b] if accept_len is 0):
+ *                the token the LLM regenerates at the first rejection
+ * Malformed parent ids (>= child or < -1) are ignored, as in gsd_build_mask.
+ */
+int gsd_accept_longest_path(int32_t batch, int32_t total_nodes, int32_t max_nodes, const int32_t *node_offsets,
+                            const int32_t *parent_offsets, const int32_t *parent_idx, const int32_t *tokens,
+                            const void *logits, int dtype, int32_t vocab, int64_t row_stride, int32_t *pred,
+                            const int32_t *root_pred, int32_t *accept_len, int32_t *accept_path,
+                            int32_t *bonus_token, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSD_H */

@@ -1,0 +1,266 @@
+"""Thin Python binding of libgsd (include/gsd.h): the MI355X verification hot path of Graph-structured
+Speculative Decoding.  Argument marshalling only: torch supplies device memory and the stream, every step of
+the path runs in the library's HIP kernels.  There is no CPU fallback; a missing library raises.
+
+    gsd_build_mask, gsd_dag_attention, gsd_node_argmax, gsd_accept_longest_path
+
+mirror the C entry points of the same names.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libgsd.so")
+
+GSD_OK = 0
+GSD_ERR_INVALID_ARG, GSD_ERR_NOT_TOPOLOGICAL, GSD_ERR_UNSUPPORTED, GSD_ERR_WORKSPACE, GSD_ERR_HIP = 1, 2, 3, 4, 5
+GSD_F32, GSD_BF16 = 0, 1
+GSD_MAX_NODES_PER_SEQ = 512
+
+EXPORTS = ("gsd_status_string", "gsd_last_error", "gsd_version", "gsd_build_mask", "gsd_dag_attention_workspace",
+           "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_node_argmax", "gsd_accept_longest_path")
+
+
+class GsdError(RuntimeError):
+    def __init__(self, status: int, detail: str):
+        super().__init__(f"libgsd status {status}: {detail}")
+        self.status = status
+
+
+class AttnDesc(ctypes.Structure):
+    """Mirror of struct gsd_attn_desc."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("total_nodes", ctypes.c_int32), ("max_nodes", ctypes.c_int32),
+        ("max_prefix", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("words_per_row", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("q", ctypes.c_void_p), ("o", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("k", ctypes.c_void_p),
+        ("v", ctypes.c_void_p), ("kv_offsets", ctypes.c_void_p), ("prefix_lens", ctypes.c_void_p),
+        ("node_offsets", ctypes.c_void_p), ("mask", ctypes.c_void_p),
+        ("q_token_stride", ctypes.c_int64), ("q_head_stride", ctypes.c_int64),
+        ("o_token_stride", ctypes.c_int64), ("o_head_stride", ctypes.c_int64),
+        ("kv_token_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+_lib = None
+
+
+def _load_hip_runtime():
+    """libgsd.so is linked without a HIP runtime of its own: it must run on the runtime that owns torch's
+    device memory and streams.  Make that runtime's symbols globally visible before libgsd is loaded."""
+    import torch
+    candidates = [os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"),
+                  "/opt/rocm/lib/libamdhip64.so"]
+    for path in candidates:
+        if os.path.exists(path):
+            ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
+            return path
+    raise RuntimeError("no HIP runtime (libamdhip64.so) found next to torch or under /opt/rocm")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libgsd.so (built in-tree by paper_2407_16207_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_16207_amd.build` "
+                               "(there is no fallback path)")
+        _load_hip_runtime()
+        lib = ctypes.CDLL(LIB_PATH)
+        for name in ("gsd_status_string", "gsd_last_error", "gsd_version"):
+            getattr(lib, name).restype = ctypes.c_char_p
+        lib.gsd_dag_attention_workspace.restype = ctypes.c_size_t
+        lib.gsd_dag_attention_workspace.argtypes = [ctypes.POINTER(AttnDesc)]
+        lib.gsd_dag_attention_splits.argtypes = [ctypes.POINTER(AttnDesc)]
+        lib.gsd_dag_attention.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_void_p]
+        i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        lib.gsd_build_mask.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp]
+        lib.gsd_node_argmax.argtypes = [i32, i32, ctypes.c_int, vp, i64, vp, vp]
+        lib.gsd_accept_longest_path.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_int, i32, i64, vp, vp,
+                                                vp, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _check(status: int):
+    if status != GSD_OK:
+        lib = load_library()
+        detail = lib.gsd_last_error().decode() or lib.gsd_status_string(status).decode()
+        raise GsdError(status, detail)
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return GSD_F32
+    if t.dtype == torch.bfloat16:
+        return GSD_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _require(t, dtype, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def gsd_build_mask(node_offsets, parent_offsets, parent_idx, max_nodes: int, words_per_row: int | None = None,
+                   mask=None, dag_error_flag=None, stream=None):
+    """mask[T, W] (int64 storage of the uint64 words) from the packed token graph.  See gsd_build_mask in gsd.h."""
+    import torch
+    for t, name in ((node_offsets, "node_offsets"), (parent_offsets, "parent_offsets"), (parent_idx, "parent_idx")):
+        _require(t, torch.int32, name)
+    batch = node_offsets.numel() - 1
+    total = parent_offsets.numel() - 1
+    W = (max_nodes + 63) // 64 if words_per_row is None else int(words_per_row)
+    if mask is None:
+        mask = torch.empty((total, W), dtype=torch.int64, device=node_offsets.device)
+    else:
+        _require(mask, torch.int64, "mask")
+        if mask.numel() != total * W:
+            raise ValueError("mask has the wrong size")
+    if dag_error_flag is not None:
+        _require(dag_error_flag, torch.int32, "dag_error_flag")
+    _check(load_library().gsd_build_mask(batch, max_nodes, W, _ptr(node_offsets), _ptr(parent_offsets),
+                                         _ptr(parent_idx), _ptr(mask), _ptr(dag_error_flag), _stream_ptr(stream)))
+    return mask
+
+
+def make_attn_desc(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_nodes: int, max_prefix: int,
+                   softmax_scale: float, out=None, lse=None, num_splits: int = 0, workspace=None) -> AttnDesc:
+    import torch
+    code = _dtype_code(q)
+    for t, name in ((q, "q"), (k, "k"), (v, "v")):
+        if not t.is_cuda or t.dim() != 3 or t.stride(2) != 1 or _dtype_code(t) != code:
+            raise ValueError(f"{name} must be a GPU tensor [rows, heads, head_dim] with a contiguous last dim")
+    if k.stride() != v.stride() or k.shape != v.shape:
+        raise ValueError("k and v must share shape and strides")
+    _require(kv_offsets, torch.int64, "kv_offsets")
+    _require(prefix_lens, torch.int32, "prefix_lens")
+    _require(node_offsets, torch.int32, "node_offsets")
+    _require(mask, torch.int64, "mask")
+    d = AttnDesc()
+    d.batch = prefix_lens.numel()
+    d.total_nodes, d.num_q_heads, d.head_dim = q.shape
+    d.num_kv_heads = k.shape[1]
+    d.max_nodes, d.max_prefix = int(max_nodes), int(max_prefix)
+    d.dtype = code
+    d.words_per_row = mask.shape[1]
+    d.num_splits = int(num_splits)
+    d.softmax_scale = float(softmax_scale)
+    d.q, d.k, d.v = q.data_ptr(), k.data_ptr(), v.data_ptr()
+    d.o = out.data_ptr() if out is not None else None
+    d.lse = lse.data_ptr() if lse is not None else None
+    d.kv_offsets, d.prefix_lens, d.node_offsets, d.mask = (kv_offsets.data_ptr(), prefix_lens.data_ptr(),
+                                                           node_offsets.data_ptr(), mask.data_ptr())
+    d.q_token_stride, d.q_head_stride = q.stride(0), q.stride(1)
+    if out is not None:
+        d.o_token_stride, d.o_head_stride = out.stride(0), out.stride(1)
+    d.kv_token_stride, d.kv_head_stride = k.stride(0), k.stride(1)
+    if workspace is not None:
+        d.workspace, d.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    return d
+
+
+def gsd_dag_attention_workspace(desc: AttnDesc) -> int:
+    n = load_library().gsd_dag_attention_workspace(ctypes.byref(desc))
+    if n == ctypes.c_size_t(-1).value:
+        _check(GSD_ERR_INVALID_ARG)
+    return n
+
+
+def gsd_dag_attention_splits(desc: AttnDesc) -> int:
+    return load_library().gsd_dag_attention_splits(ctypes.byref(desc))
+
+
+def gsd_dag_attention(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_nodes: int, max_prefix: int,
+                      softmax_scale: float, out=None, lse=None, num_splits: int = 0, workspace=None, stream=None,
+                      return_lse: bool = False):
+    """DAG-masked attention of every packed node; returns out (same dtype/shape as q).  See gsd.h."""
+    import torch
+    if out is None:
+        out = torch.empty_like(q, memory_format=torch.contiguous_format)
+    if return_lse and lse is None:
+        lse = torch.empty((q.shape[0], q.shape[1]), dtype=torch.float32, device=q.device)
+    if lse is not None:
+        _require(lse, torch.float32, "lse")
+    desc = make_attn_desc(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_nodes, max_prefix, softmax_scale,
+                          out=out, lse=lse, num_splits=num_splits, workspace=workspace)
+    if workspace is None:
+        need = gsd_dag_attention_workspace(desc)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+            desc.workspace, desc.workspace_bytes = workspace.data_ptr(), need
+    _check(load_library().gsd_dag_attention(ctypes.byref(desc), _stream_ptr(stream)))
+    return (out, lse) if return_lse else out
+
+
+def gsd_dag_attention_desc(desc: AttnDesc, stream=None):
+    """Launch from a prepared descriptor (no allocation, for timing loops)."""
+    _check(load_library().gsd_dag_attention(ctypes.byref(desc), _stream_ptr(stream)))
+
+
+def gsd_node_argmax(logits, pred=None, stream=None):
+    """pred[r] = lowest index of the row maximum of logits[r].  See gsd_node_argmax in gsd.h."""
+    import torch
+    if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be a GPU tensor [rows, vocab] with a contiguous last dim")
+    rows, vocab = logits.shape
+    if pred is None:
+        pred = torch.empty(rows, dtype=torch.int32, device=logits.device)
+    _require(pred, torch.int32, "pred")
+    _check(load_library().gsd_node_argmax(rows, vocab, _dtype_code(logits), _ptr(logits), logits.stride(0),
+                                          _ptr(pred), _stream_ptr(stream)))
+    return pred
+
+
+def gsd_accept_longest_path(node_offsets, parent_offsets, parent_idx, tokens, root_pred, max_nodes: int,
+                            logits=None, pred=None, accept_len=None, accept_path=None, bonus_token=None,
+                            stream=None):
+    """Longest accepted root path per sequence; returns (accept_len[B], accept_path[B, max_nodes], bonus[B], pred).
+    With `logits` the per-node argmax runs first on the same stream.  See gsd_accept_longest_path in gsd.h."""
+    import torch
+    for t, name in ((node_offsets, "node_offsets"), (parent_offsets, "parent_offsets"), (parent_idx, "parent_idx"),
+                    (tokens, "tokens"), (root_pred, "root_pred")):
+        _require(t, torch.int32, name)
+    batch = node_offsets.numel() - 1
+    total = tokens.numel()
+    dev = tokens.device
+    if pred is None:
+        if logits is None:
+            raise ValueError("give logits or pred")
+        pred = torch.empty(total, dtype=torch.int32, device=dev)
+    _require(pred, torch.int32, "pred")
+    accept_len = torch.empty(batch, dtype=torch.int32, device=dev) if accept_len is None else accept_len
+    accept_path = torch.empty((batch, max_nodes), dtype=torch.int32, device=dev) if accept_path is None else accept_path
+    bonus_token = torch.empty(batch, dtype=torch.int32, device=dev) if bonus_token is None else bonus_token
+    for t, name in ((accept_len, "accept_len"), (accept_path, "accept_path"), (bonus_token, "bonus_token")):
+        _require(t, torch.int32, name)
+    if logits is not None:
+        if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1 or logits.shape[0] != total:
+            raise ValueError("logits must be a GPU tensor [T, vocab] with a contiguous last dim")
+        dtype, vocab, stride = _dtype_code(logits), logits.shape[1], logits.stride(0)
+    else:
+        dtype, vocab, stride = GSD_F32, 0, 0
+    _check(load_library().gsd_accept_longest_path(batch, total, max_nodes, _ptr(node_offsets), _ptr(parent_offsets),
+                                                  _ptr(parent_idx), _ptr(tokens), _ptr(logits), dtype, vocab, stride,
+                                                  _ptr(pred), _ptr(root_pred), _ptr(accept_len), _ptr(accept_path),
+                                                  _ptr(bonus_token), _stream_ptr(stream)))
+    return accept_len, accept_path, bonus_token, pred

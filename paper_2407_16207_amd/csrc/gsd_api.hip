@@ -1,0 +1,163 @@
+// C ABI of libgsd: argument validation, error reporting and dispatch to the kernel launchers.
+// Everything a host can check is checked here, before any launch, so a bad call leaves its outputs untouched.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "gsd_internal.h"
+
+namespace {
+
+thread_local char g_last_error[256] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_last_error, sizeof g_last_error, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_fail(hipError_t err, const char *what) {
+    return fail(GSD_ERR_HIP, "%s: %s", what, hipGetErrorString(err));
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+int check_attn_desc(const gsd_attn_desc *d) {
+    if (!d) return fail(GSD_ERR_INVALID_ARG, "descriptor is NULL");
+    if (d->batch < 1 || d->total_nodes < 1 || d->max_nodes < 1 || d->max_prefix < 0)
+        return fail(GSD_ERR_INVALID_ARG, "batch, total_nodes, max_nodes must be >= 1 and max_prefix >= 0");
+    if (d->num_q_heads < 1 || d->num_kv_heads < 1 || d->num_q_heads % d->num_kv_heads != 0)
+        return fail(GSD_ERR_INVALID_ARG, "num_kv_heads (%d) must divide num_q_heads (%d)", d->num_kv_heads,
+                    d->num_q_heads);
+    if (d->dtype != GSD_F32 && d->dtype != GSD_BF16) return fail(GSD_ERR_UNSUPPORTED, "dtype %d", d->dtype);
+    if (d->head_dim != 64 && d->head_dim != 128)
+        return fail(GSD_ERR_UNSUPPORTED, "head_dim %d (supported: 64, 128)", d->head_dim);
+    if (d->max_nodes > GSD_MAX_NODES_PER_SEQ)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", d->max_nodes, GSD_MAX_NODES_PER_SEQ);
+    if (d->words_per_row < (d->max_nodes + 63) / 64)
+        return fail(GSD_ERR_INVALID_ARG, "words_per_row %d too small for max_nodes %d", d->words_per_row,
+                    d->max_nodes);
+    if (d->num_splits < 0) return fail(GSD_ERR_INVALID_ARG, "num_splits must be >= 0");
+    if (!(d->softmax_scale > 0.f) || !(d->softmax_scale < 1e6f))
+        return fail(GSD_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
+    return GSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *gsd_status_string(int status) {
+    switch (status) {
+        case GSD_OK: return "ok";
+        case GSD_ERR_INVALID_ARG: return "invalid argument";
+        case GSD_ERR_NOT_TOPOLOGICAL: return "graph is not in topological order";
+        case GSD_ERR_UNSUPPORTED: return "unsupported configuration";
+        case GSD_ERR_WORKSPACE: return "workspace too small";
+        case GSD_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char *gsd_last_error(void) { return g_last_error; }
+
+const char *gsd_version(void) { return "gsd-gfx950 0.1"; }
+
+int gsd_build_mask(int32_t batch, int32_t max_nodes, int32_t words_per_row, const int32_t *node_offsets,
+                   const int32_t *parent_offsets, const int32_t *parent_idx, uint64_t *mask,
+                   int32_t *dag_error_flag, void *hip_stream) {
+    if (batch < 1 || max_nodes < 1) return fail(GSD_ERR_INVALID_ARG, "batch and max_nodes must be >= 1");
+    if (max_nodes > GSD_MAX_NODES_PER_SEQ)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", max_nodes, GSD_MAX_NODES_PER_SEQ);
+    if (words_per_row < (max_nodes + 63) / 64)
+        return fail(GSD_ERR_INVALID_ARG, "words_per_row %d too small for max_nodes %d", words_per_row, max_nodes);
+    if (size_t(max_nodes) * words_per_row * sizeof(uint64_t) > 32768)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes * words_per_row exceeds 4096 words");
+    if (!node_offsets || !parent_offsets || !parent_idx || !mask)
+        return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    hipError_t err = gsd::launch_build_mask(batch, max_nodes, words_per_row, node_offsets, parent_offsets,
+                                            parent_idx, mask, dag_error_flag, (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_build_mask launch");
+}
+
+int gsd_dag_attention_splits(const gsd_attn_desc *desc) {
+    if (check_attn_desc(desc) != GSD_OK) return -1;
+    return desc->dtype == GSD_BF16 ? gsd::attention_bf16_splits(*desc) : 1;
+}
+
+size_t gsd_dag_attention_workspace(const gsd_attn_desc *desc) {
+    if (check_attn_desc(desc) != GSD_OK) return (size_t)-1;
+    if (desc->dtype != GSD_BF16) return 0;
+    return gsd::attention_bf16_workspace(*desc, gsd::attention_bf16_splits(*desc));
+}
+
+int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream) {
+    int rc = check_attn_desc(desc);
+    if (rc != GSD_OK) return rc;
+    const gsd_attn_desc &d = *desc;
+    if (!d.q || !d.o || !d.k || !d.v || !d.kv_offsets || !d.prefix_lens || !d.node_offsets || !d.mask)
+        return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    const int64_t align = d.dtype == GSD_BF16 ? 8 : 4;
+    if (!aligned16(d.q) || !aligned16(d.o) || !aligned16(d.k) || !aligned16(d.v))
+        return fail(GSD_ERR_INVALID_ARG, "q, o, k, v must be 16-byte aligned");
+    const int64_t strides[6] = {d.q_token_stride, d.q_head_stride, d.o_token_stride,
+                                d.o_head_stride, d.kv_token_stride, d.kv_head_stride};
+    for (int64_t s : strides)
+        if (s < d.head_dim || s % align != 0)
+            return fail(GSD_ERR_INVALID_ARG, "strides must be >= head_dim and multiples of %lld elements",
+                        (long long)align);
+    if (int64_t(d.total_nodes) * d.num_q_heads > (int64_t(1) << 30))
+        return fail(GSD_ERR_UNSUPPORTED, "total_nodes * num_q_heads too large");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipError_t err;
+    if (d.dtype == GSD_F32) {
+        err = gsd::launch_attention_f32(d, stream);
+    } else {
+        const int splits = gsd::attention_bf16_splits(d);
+        const size_t need = gsd::attention_bf16_workspace(d, splits);
+        if (need > 0 && (!d.workspace || d.workspace_bytes < need))
+            return fail(GSD_ERR_WORKSPACE, "workspace of %zu bytes needed for %d KV splits, %zu given", need, splits,
+                        d.workspace ? d.workspace_bytes : size_t(0));
+        if (need > 0 && !aligned16(d.workspace)) return fail(GSD_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+        err = gsd::launch_attention_bf16(d, splits, stream);
+    }
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_dag_attention launch");
+}
+
+int gsd_node_argmax(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
+                    int32_t *pred, void *hip_stream) {
+    if (rows < 1 || vocab < 1) return fail(GSD_ERR_INVALID_ARG, "rows and vocab must be >= 1");
+    if (dtype != GSD_F32 && dtype != GSD_BF16) return fail(GSD_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (!logits || !pred) return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    if (row_stride < vocab) return fail(GSD_ERR_INVALID_ARG, "row_stride %lld < vocab %d", (long long)row_stride, vocab);
+    const uintptr_t elt = dtype == GSD_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(logits) % elt != 0) return fail(GSD_ERR_INVALID_ARG, "logits misaligned");
+    hipError_t err = gsd::launch_node_argmax(rows, vocab, dtype, logits, row_stride, pred, (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_node_argmax launch");
+}
+
+int gsd_accept_longest_path(int32_t batch, int32_t total_nodes, int32_t max_nodes, const int32_t *node_offsets,
+                            const int32_t *parent_offsets, const int32_t *parent_idx, const int32_t *tokens,
+                            const void *logits, int dtype, int32_t vocab, int64_t row_stride, int32_t *pred,
+                            const int32_t *root_pred, int32_t *accept_len, int32_t *accept_path,
+                            int32_t *bonus_token, void *hip_stream) {
+    if (batch < 1 || max_nodes < 1 || total_nodes < 1)
+        return fail(GSD_ERR_INVALID_ARG, "batch, total_nodes and max_nodes must be >= 1");
+    if (max_nodes > GSD_MAX_NODES_PER_SEQ)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", max_nodes, GSD_MAX_NODES_PER_SEQ);
+    if (!node_offsets || !parent_offsets || !parent_idx || !tokens || !pred || !root_pred || !accept_len ||
+        !accept_path || !bonus_token)
+        return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (logits) {
+        const int rc = gsd_node_argmax(total_nodes, vocab, dtype, logits, row_stride, pred, hip_stream);
+        if (rc != GSD_OK) return rc;
+    }
+    hipError_t err = gsd::launch_accept(batch, max_nodes, node_offsets, parent_offsets, parent_idx, tokens, pred,
+                                        root_pred, accept_len, accept_path, bonus_token, stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_accept_longest_path launch");
+}
+
+}  // extern "C"

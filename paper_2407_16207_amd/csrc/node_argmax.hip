@@ -1,0 +1,121 @@
+// Per-node vocabulary argmax of the verifier logits: the token the LLM itself would generate after each
+// node (paper Section 3, deterministic verification).  Pure HBM streaming: one work-group per logits row,
+// 16-byte loads, a (value, index) pair per lane, wave shuffles and one LDS hop to reduce.  The lowest index
+// wins ties exactly (values are compared as stored); NaN never wins; an all-NaN row gives 0.
+#include "gsd_internal.h"
+
+namespace gsd {
+
+struct Best {
+    float val;
+    int32_t idx;   // INT32_MAX = nothing seen yet
+};
+
+__device__ __forceinline__ void consider(Best &b, float x, int32_t idx) {
+    // elements are offered in ascending index order within a lane, so strict > keeps the first occurrence;
+    // the equality arm only matters for the -inf start value.
+    if (x > b.val || (x == b.val && idx < b.idx)) {
+        b.val = x;
+        b.idx = idx;
+    }
+}
+
+__device__ __forceinline__ Best merge(Best a, Best o) {
+    if (o.val > a.val || (o.val == a.val && o.idx < a.idx)) return o;
+    return a;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+template <int THREADS, bool BF16>
+__global__ __launch_bounds__(THREADS) void node_argmax_kernel(int32_t vocab, const void *__restrict__ logits,
+                                                              int64_t row_stride, int32_t *__restrict__ pred) {
+    constexpr int ELT = BF16 ? 2 : 4;
+    constexpr int PER_VEC = 16 / ELT;
+    const int64_t row = blockIdx.x;
+    const char *row_ptr = reinterpret_cast<const char *>(logits) + row * row_stride * ELT;
+    Best best{-__builtin_inff(), 0x7fffffff};
+
+    // scalar head up to the first 16-byte boundary, vector body, scalar tail
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(row_ptr);
+    int head = int(((16 - (addr & 15)) & 15) / ELT);
+    if (head > vocab) head = vocab;
+    const int nvec = (vocab - head) / PER_VEC;
+    const int tail_start = head + nvec * PER_VEC;
+
+    auto scalar_at = [&](int32_t i) -> float {
+        if (BF16) return __uint_as_float(uint32_t(reinterpret_cast<const uint16_t *>(row_ptr)[i]) << 16);
+        return reinterpret_cast<const float *>(row_ptr)[i];
+    };
+    if (int(threadIdx.x) < head) consider(best, scalar_at(threadIdx.x), threadIdx.x);
+
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 *vec = reinterpret_cast<const u32x4 *>(row_ptr + size_t(head) * ELT);
+    for (int c = threadIdx.x; c < nvec; c += THREADS) {
+        const u32x4 w = __builtin_nontemporal_load(vec + c);
+        const int32_t i0 = head + c * PER_VEC;
+        if (BF16) {
+            consider(best, bf16_lo(w.x), i0 + 0);
+            consider(best, bf16_hi(w.x), i0 + 1);
+            consider(best, bf16_lo(w.y), i0 + 2);
+            consider(best, bf16_hi(w.y), i0 + 3);
+            consider(best, bf16_lo(w.z), i0 + 4);
+            consider(best, bf16_hi(w.z), i0 + 5);
+            consider(best, bf16_lo(w.w), i0 + 6);
+            consider(best, bf16_hi(w.w), i0 + 7);
+        } else {
+            consider(best, __uint_as_float(w.x), i0 + 0);
+            consider(best, __uint_as_float(w.y), i0 + 1);
+            consider(best, __uint_as_float(w.z), i0 + 2);
+            consider(best, __uint_as_float(w.w), i0 + 3);
+        }
+    }
+    {
+        const int i = tail_start + threadIdx.x;
+        if (i < vocab) consider(best, scalar_at(i), i);
+    }
+
+    for (int off = 32; off > 0; off >>= 1) {
+        Best o;
+        o.val = __shfl_xor(best.val, off, 64);
+        o.idx = __shfl_xor(best.idx, off, 64);
+        best = merge(best, o);
+    }
+    __shared__ float s_val[THREADS / 64];
+    __shared__ int32_t s_idx[THREADS / 64];
+    if ((threadIdx.x & 63) == 0) {
+        s_val[threadIdx.x >> 6] = best.val;
+        s_idx[threadIdx.x >> 6] = best.idx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        Best r{s_val[0], s_idx[0]};
+        for (int w = 1; w < THREADS / 64; ++w) r = merge(r, Best{s_val[w], s_idx[w]});
+        pred[row] = (r.idx == 0x7fffffff) ? 0 : r.idx;
+    }
+}
+
+hipError_t launch_node_argmax(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
+                              int32_t *pred, hipStream_t stream) {
+    // Few rows: large work-groups so each row still has many loads in flight.
+    const bool big = rows < 1024;
+    if (dtype == GSD_BF16) {
+        if (big)
+            hipLaunchKernelGGL((node_argmax_kernel<1024, true>), dim3(rows), dim3(1024), 0, stream, vocab, logits,
+                               row_stride, pred);
+        else
+            hipLaunchKernelGGL((node_argmax_kernel<256, true>), dim3(rows), dim3(256), 0, stream, vocab, logits,
+                               row_stride, pred);
+    } else {
+        if (big)
+            hipLaunchKernelGGL((node_argmax_kernel<1024, false>), dim3(rows), dim3(1024), 0, stream, vocab, logits,
+                               row_stride, pred);
+        else
+            hipLaunchKernelGGL((node_argmax_kernel<256, false>), dim3(rows), dim3(256), 0, stream, vocab, logits,
+                               row_stride, pred);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace gsd
