@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the GSD verify hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input already resident in HBM:
+    gsd_build_mask -> gsd_dag_attention -> gsd_accept_longest_path (per-node argmax + longest accepted path)
+all on one stream, through the C ABI.  The workload is the LLaMA-2-70B-shaped configuration (config 4: batch 8,
+64 query / 8 KV heads, head_dim 128, KV prefix 4096, 256 draft nodes per sequence, bf16) unless --config says
+otherwise.  Prints ONE JSON line: whole-step throughput in draft nodes verified per second, the attention
+kernel's achieved TFLOP/s against the bf16 matrix-core peak ("roofline"), and the CPU oracle timed on a
+bounded sample of the same workload on this host ("cpu_baseline", a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix-core peak
+HBM_PEAK_GBS = 8000.0              # MI355X HBM3E peak
+
+
+def popcount_rows(mask_np):
+    import numpy as np
+    return np.unpackbits(mask_np.view(np.uint8), axis=1).sum(axis=1)
+
+
+def measured_traffic(cfg_name: str):
+    """HBM bytes per attention launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "attention_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(cfg_name, {}).get("traffic_bytes_per_launch")
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(w, sample_nodes: int):
+    """The oracle, as it stands, on a bounded sample: `sample_nodes` nodes (all heads) spread over the batch for
+    attention and argmax, the mask and acceptance steps on the full batch (scaled to the sample's share)."""
+    import numpy as np
+    from oracle import gsd_ref
+
+    cfg = w.cfg
+    T = w.total_nodes
+    rng = np.random.default_rng(0)
+    nodes = np.sort(rng.choice(T, size=min(sample_nodes, T), replace=False))
+    S = len(nodes)
+    t0 = time.perf_counter()
+    mask, _ = gsd_ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    t_mask = time.perf_counter() - t0
+    b_of = np.searchsorted(w.node_offsets, nodes, side="right") - 1
+    i_of = nodes - w.node_offsets[b_of]
+    H = cfg.num_q_heads
+    rb, ri = np.repeat(b_of, H), np.repeat(i_of, H)
+    rh = np.tile(np.arange(H), S)
+    t0 = time.perf_counter()
+    gsd_ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale,
+                          rows=(rb, ri, rh))
+    t_attn = time.perf_counter() - t0
+    sample_logits = np.ascontiguousarray(w.logits[nodes])
+    t0 = time.perf_counter()
+    gsd_ref.node_argmax(sample_logits)
+    t_argmax = time.perf_counter() - t0
+    pred = gsd_ref.node_argmax(w.logits)
+    t0 = time.perf_counter()
+    gsd_ref.accept_longest_path(w.node_offsets, w.parent_offsets, w.parent_idx, w.tokens, pred, w.root_pred)
+    t_accept = time.perf_counter() - t0
+    total = t_attn + t_argmax + (t_mask + t_accept) * S / T
+    return {"value": S / total, "unit": "nodes/s", "cores": gsd_ref.num_threads(), "kind": "oracle",
+            "sample": f"{S} of {T} draft nodes (all {H} heads) for attention+argmax, {t_attn + t_argmax:.1f} s; "
+                      f"mask and acceptance on the full batch, scaled by {S}/{T}",
+            "seconds": {"mask_full": t_mask, "attention_sample": t_attn, "argmax_sample": t_argmax,
+                        "accept_full": t_accept}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=4, help="workload config 1..5 (default: 4, the 70B-shaped one)")
+    ap.add_argument("--cpu-sample-nodes", type=int, default=2048)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--splits", type=int, default=0, help="force the attention KV split count (0 = library's choice)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    import paper_2407_16207_amd as gsd
+    from paper_2407_16207_amd.workload import make_workload
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    gsd.load_library()
+
+    t_gen = time.perf_counter()
+    w = make_workload(args.config)
+    cfg = w.cfg
+    t_gen = time.perf_counter() - t_gen
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    node_offsets, parent_offsets, parent_idx = dev(w.node_offsets), dev(w.parent_offsets), dev(w.parent_idx)
+    tokens, root_pred = dev(w.tokens), dev(w.root_pred)
+    q, k, v, logits = dev(w.q), dev(w.k), dev(w.v), dev(w.logits)
+    kv_offsets, prefix_lens = dev(w.kv_offsets), dev(w.prefix_lens)
+    T, N, W = w.total_nodes, w.max_nodes, w.words_per_row
+    B = cfg.batch
+
+    # every output and scratch buffer is allocated once, outside the timed region
+    mask = torch.empty((T, W), dtype=torch.int64, device="cuda")
+    out = torch.empty_like(q)
+    pred = torch.empty(T, dtype=torch.int32, device="cuda")
+    accept_len = torch.empty(B, dtype=torch.int32, device="cuda")
+    accept_path = torch.empty((B, N), dtype=torch.int32, device="cuda")
+    bonus = torch.empty(B, dtype=torch.int32, device="cuda")
+    desc = gsd.make_attn_desc(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, N, int(w.prefix_lens.max()),
+                              w.softmax_scale, out=out, num_splits=args.splits)
+    need = gsd.gsd_dag_attention_workspace(desc)
+    workspace = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    desc.workspace, desc.workspace_bytes = workspace.data_ptr(), need
+    splits = gsd.gsd_dag_attention_splits(desc)
+
+    stream = torch.cuda.current_stream()
+
+    def step(events=None):
+        if events:
+            events[0].record(stream)
+        gsd.gsd_build_mask(node_offsets, parent_offsets, parent_idx, N, words_per_row=W, mask=mask)
+        if events:
+            events[1].record(stream)
+        gsd.gsd_dag_attention_desc(desc)
+        if events:
+            events[2].record(stream)
+        gsd.gsd_accept_longest_path(node_offsets, parent_offsets, parent_idx, tokens, root_pred, N, logits=logits,
+                                    pred=pred, accept_len=accept_len, accept_path=accept_path, bonus_token=bonus)
+        if events:
+            events[3].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])      # ms
+    mask_ms, attn_ms, accept_ms = stage.mean(axis=0)
+
+    # argmax alone (the HBM-bound part of the acceptance call), on the same stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = max(5, min(50, args.steps))
+    e0.record(stream)
+    for _ in range(reps):
+        gsd.gsd_node_argmax(logits, pred=pred)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    argmax_ms = e0.elapsed_time(e1) / reps
+
+    # algorithmic work of the attention launch: 4*D flops per visible (query row, key) pair
+    vis = popcount_rows(mask.cpu().numpy().view(np.uint64))
+    per_node_keys = np.repeat(w.prefix_lens.astype(np.int64), np.diff(w.node_offsets)) + vis
+    flops = 4.0 * cfg.head_dim * cfg.num_q_heads * float(per_node_keys.sum())
+    attn_tflops = flops / (attn_ms * 1e-3) / 1e12
+    logits_bytes = float(T) * cfg.vocab * logits.element_size()
+    argmax_gbs = logits_bytes / (argmax_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": "draft nodes verified/s (whole verify hot path: mask + DAG-masked attention + argmax + "
+                  "longest accepted path, one attention layer)",
+        "value": T / (ms_per_step * 1e-3),
+        "unit": "nodes/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": B, "q_heads": cfg.num_q_heads, "kv_heads": cfg.num_kv_heads,
+                   "head_dim": cfg.head_dim, "kv_prefix": [int(w.prefix_lens.min()), int(w.prefix_lens.max())],
+                   "draft_nodes_per_seq": N, "total_nodes": T, "vocab": cfg.vocab, "kv_splits": splits,
+                   "seed": w.seed},
+        "roofline": {"kernel": "dag_attention_bf16_kernel", "bound": "mfma", "achieved": attn_tflops,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": measured_traffic(cfg.name), "algorithmic_flops_per_launch": flops,
+                     "avg_launch_ms": float(attn_ms)},
+        "roofline_argmax": {"kernel": "node_argmax_kernel", "bound": "hbm", "achieved": argmax_gbs,
+                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": argmax_gbs / HBM_PEAK_GBS,
+                            "algorithmic_bytes_per_launch": logits_bytes, "avg_launch_ms": float(argmax_ms)},
+        "attention_tflops": attn_tflops,
+        "attention_pct_bf16_mfma_peak": 100.0 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+        "stage_ms": {"mask": float(mask_ms), "attention": float(attn_ms), "argmax_plus_accept": float(accept_ms),
+                     "argmax_alone": float(argmax_ms)},
+        "accepted_lengths": accept_len.cpu().tolist(),
+        "paper_context": "GSD end-to-end speedup 1.73x-1.96x over autoregressive decoding (LLaMA-2-70b, hardware "
+                         "not stated in the paper); context only, not comparable to this per-layer kernel metric",
+    }
+    if cfg.dtype != "bf16":
+        result["roofline"]["kernel"] = "dag_attention_f32_kernel"
+        result["roofline"]["bound"] = "alu"
+        result["roofline"]["peak"] = 157.3
+        result["roofline"]["frac"] = attn_tflops / 157.3
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_nodes)
+        result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -29,6 +29,9 @@
  * uint16 (dtype 1); both are widened exactly to fp64 before any arithmetic.
  */
 #include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -42,6 +45,15 @@ static double load_elt(const void *base, int dtype, int64_t idx) {
     float f;
     memcpy(&f, &bits, sizeof f);
     return (double)f;
+}
+
+/* Threads the row loops will use (for reporting next to timings). */
+int gsd_ref_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }
 
 /* ------------------------------------------------------------------------------------------------ mask */

@@ -35,6 +35,11 @@ def _load():
     return _lib
 
 
+def num_threads() -> int:
+    """Threads the oracle's row loops run on (OpenMP's current maximum)."""
+    return int(_load().gsd_ref_num_threads())
+
+
 def _p(a: np.ndarray):
     return a.ctypes.data_as(ctypes.c_void_p)
 
