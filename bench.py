@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--cpu-sample-nodes", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--splits", type=int, default=0, help="force the attention KV split count (0 = library's choice)")
+    ap.add_argument("--profile-stage", choices=["attention", "argmax", "mask", "accept", "copy"], default=None,
+                    help="profiling aid: launch only this stage --steps times (after one full step) and print a "
+                         "short JSON line; 'copy' runs a plain 256 MiB device copy for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -148,6 +151,33 @@ def main():
                                     pred=pred, accept_len=accept_len, accept_path=accept_path, bonus_token=bonus)
         if events:
             events[3].record(stream)
+
+    if args.profile_stage:
+        step()
+        torch.cuda.synchronize()
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda") if args.profile_stage == "copy" else None
+        dst = torch.empty_like(src) if src is not None else None
+        launch = {
+            "attention": lambda: gsd.gsd_dag_attention_desc(desc),
+            "argmax": lambda: gsd.gsd_node_argmax(logits, pred=pred),
+            "mask": lambda: gsd.gsd_build_mask(node_offsets, parent_offsets, parent_idx, N, words_per_row=W, mask=mask),
+            "accept": lambda: gsd.gsd_accept_longest_path(node_offsets, parent_offsets, parent_idx, tokens, root_pred,
+                                                          N, pred=pred, accept_len=accept_len,
+                                                          accept_path=accept_path, bonus_token=bonus),
+            "copy": lambda: dst.copy_(src),
+        }[args.profile_stage]
+        for _ in range(args.warmup):
+            launch()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(args.steps):
+            launch()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_stage": args.profile_stage, "workload": cfg.name, "launches": args.steps,
+                          "avg_launch_ms": e0.elapsed_time(e1) / args.steps,
+                          "copy_bytes": (256 << 20) if src is not None else None}), flush=True)
+        return
 
     for _ in range(args.warmup):
         step()

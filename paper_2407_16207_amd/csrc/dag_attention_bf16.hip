@@ -19,6 +19,8 @@
 //
 // Small problems are split along the KV axis (gsd_attn_desc.num_splits); a split writes unnormalised fp32
 // partials (O, running max, running sum) and a second kernel merges them in split order.
+#include <type_traits>
+
 #include "gsd_internal.h"
 
 namespace gsd {
@@ -66,24 +68,39 @@ struct Lds {
     static constexpr int kKBytes = kKeysPerTile * kKRowBytes;
     static constexpr int kVRowBytes = D * 4;                      // one key PAIR x D channels, 4 bytes each
     static constexpr int kVBytes = (kKeysPerTile / 2) * kVRowBytes;
-    static constexpr int kTotal = kKBytes + kVBytes;
+    static constexpr int kTotal = 2 * (kKBytes + kVBytes);        // K and V are both double-buffered
 };
 
 // position of actual key row r (0..63) inside the LDS K tile: bits 2 and 3 of r swapped (see file comment)
 __device__ __forceinline__ int k_lds_row(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
+// Nothing may be moved across this point by the instruction scheduler: the loop body below is laid out by hand
+// as slices of one matrix instruction, one or two LDS reads for a later slice and a few softmax operations, so
+// that the matrix pipe and the vector ALU of a wave run side by side.
+#define GSD_SLICE_END() __builtin_amdgcn_sched_barrier(0)
+
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// max over the two 32-lane halves of a wavefront, in every lane
+__device__ __forceinline__ float max_across_halves(float x) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const AttnParams p) {
     constexpr int KS = D / 16;          // k-steps of the first contraction
     constexpr int MBD = D / 32;         // 32-channel blocks of the output
+    constexpr int NQK = 2 * KS;         // matrix instructions of S^T = K Q^T per tile
+    constexpr int NPV = 4 * MBD;        // matrix instructions of O^T += V^T P^T per tile
     constexpr int CHUNKS = D / 8;       // 16-byte chunks per K/V row
     constexpr int ROWS_PER_PASS = kThreads / CHUNKS;
     constexpr int K_PASSES = kKeysPerTile / ROWS_PER_PASS;
     constexpr int V_PASSES = (kKeysPerTile / 2) / ROWS_PER_PASS;
     using L = Lds<D>;
     __shared__ __attribute__((aligned(16))) char lds[L::kTotal];
-    char *lds_k = lds;
-    char *lds_v = lds + L::kKBytes;
+    char *const lds_k = lds;                         // two K tiles
+    char *const lds_v = lds + 2 * L::kKBytes;        // two V tiles
 
     // ---- which piece of work: XCD-aware decode of the linear work-group id --------------------------------
     // Hardware deals consecutive work-group ids round-robin to the 8 XCDs; give every XCD a contiguous range
@@ -128,6 +145,7 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     const int per_split = (nt + p.splits - 1) / p.splits;
     const int t_begin = split * per_split;
     const int t_end = min(nt, t_begin + per_split);
+    const int full_end = min(t_end, P / kKeysPerTile);      // tiles below this index need no mask at all
 
     // draft tiles that no row of this work-group can see are skipped: bit j of `live` = tile j has a set bit
     uint64_t live = 0;
@@ -135,7 +153,16 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
         const uint64_t w = row_valid ? mrow[j] : 0;
         if (__syncthreads_or(w != 0)) live |= uint64_t(1) << (j & 63);
     }
-    auto tile_live = [&](int ti) -> bool { return ti < ntp || ((live >> ((ti - ntp) & 63)) & 1); };
+    // smallest live tile index > ti inside the split's range, or t_end
+    auto next_live = [&](int ti) __attribute__((always_inline)) -> int {
+        const int u = ti + 1;
+        if (u >= t_end) return t_end;
+        if (u < ntp) return u;
+        const uint64_t rem = live >> (u - ntp);
+        if (rem == 0) return t_end;
+        const int v = u + __builtin_ctzll(rem);
+        return v < t_end ? v : t_end;
+    };
 
     // ---- Q fragments: B operand of S^T = K Q^T; lane holds Q[row][ks*16 + 8*half .. +7] ------------------------
     bf16x8 qf[KS];
@@ -150,26 +177,30 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     for (int i = 0; i < MBD; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
-    float m_run = kMInit;
-    float l_run = 0.f;
+    float m_run = kMInit;      // running max of the raw scores, already covering the tile held in `s`
+    float l_run = 0.f;         // this lane's share of the running sum (the other half lives in lane^32)
+    float alpha = 1.f;         // pending rescale of acc_o / l_run for the tile held in `s`
+    bool need_rescale = false; // wave-uniform: some lane's max moved
 
-    // ---- global -> register staging of one K/V tile ---------------------------------------------------------
+    // ---- global -> register -> LDS staging of K/V tiles --------------------------------------------------------
     const __bf16 *k_seq = p.k + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
     const __bf16 *v_seq = p.v + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
     const int ld_row = tid / CHUNKS;
     const int ld_chunk = tid % CHUNKS;
     const int32_t last_row = P + n - 1;            // last K/V row of the sequence: loads are clamped to it
     u32x4 kreg[K_PASSES], vreg[2 * V_PASSES];
-    uint64_t word_next = 0;
 
-    auto tile_first_row = [&](int ti) -> int32_t { return ti < ntp ? ti * kKeysPerTile : P + (ti - ntp) * kKeysPerTile; };
-    auto issue_loads = [&](int ti) {
+    auto tile_first_row = [&](int ti) __attribute__((always_inline)) -> int32_t { return ti < ntp ? ti * kKeysPerTile : P + (ti - ntp) * kKeysPerTile; };
+    auto load_k = [&](int ti) __attribute__((always_inline)) {
         const int32_t r0 = tile_first_row(ti);
 #pragma unroll
         for (int ps = 0; ps < K_PASSES; ++ps) {
             const int32_t r = min(r0 + ps * ROWS_PER_PASS + ld_row, last_row);
             kreg[ps] = *reinterpret_cast<const u32x4 *>(k_seq + int64_t(r) * p.kv_ts + ld_chunk * 8);
         }
+    };
+    auto load_v = [&](int ti) __attribute__((always_inline)) {
+        const int32_t r0 = tile_first_row(ti);
 #pragma unroll
         for (int ps = 0; ps < V_PASSES; ++ps) {
             const int32_t ra = min(r0 + 2 * (ps * ROWS_PER_PASS + ld_row), last_row);
@@ -177,14 +208,17 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
             vreg[2 * ps] = *reinterpret_cast<const u32x4 *>(v_seq + int64_t(ra) * p.kv_ts + ld_chunk * 8);
             vreg[2 * ps + 1] = *reinterpret_cast<const u32x4 *>(v_seq + int64_t(rb) * p.kv_ts + ld_chunk * 8);
         }
-        if (ti >= ntp) word_next = mrow[ti - ntp];
     };
-    auto stage_to_lds = [&]() {
+    auto store_k = [&](int buf) __attribute__((always_inline)) {
+        char *base = lds_k + buf * L::kKBytes;
 #pragma unroll
         for (int ps = 0; ps < K_PASSES; ++ps) {
             const int r = ps * ROWS_PER_PASS + ld_row;
-            *reinterpret_cast<u32x4 *>(lds_k + k_lds_row(r) * L::kKRowBytes + ld_chunk * 16) = kreg[ps];
+            *reinterpret_cast<u32x4 *>(base + k_lds_row(r) * L::kKRowBytes + ld_chunk * 16) = kreg[ps];
         }
+    };
+    auto store_v = [&](int buf) __attribute__((always_inline)) {
+        char *base = lds_v + buf * L::kVBytes;
 #pragma unroll
         for (int ps = 0; ps < V_PASSES; ++ps) {
             const int pr = ps * ROWS_PER_PASS + ld_row;
@@ -198,104 +232,203 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
             hi[1] = __builtin_amdgcn_perm(c[2], a[2], 0x07060302u);
             hi[2] = __builtin_amdgcn_perm(c[3], a[3], 0x05040100u);
             hi[3] = __builtin_amdgcn_perm(c[3], a[3], 0x07060302u);
-            char *dst = lds_v + pr * L::kVRowBytes + ld_chunk * 32;
+            char *dst = base + pr * L::kVRowBytes + ld_chunk * 32;
             *reinterpret_cast<u32x4 *>(dst) = lo;
             *reinterpret_cast<u32x4 *>(dst + 16) = hi;
         }
     };
 
-    // first live tile of the range
-    int ti = t_begin;
-    while (ti < t_end && !tile_live(ti)) ++ti;
-    if (ti < t_end) issue_loads(ti);
-
-    while (ti < t_end) {
-        int tn = ti + 1;
-        while (tn < t_end && !tile_live(tn)) ++tn;
-
-        __syncthreads();                 // every wave is done reading the previous tile
-        stage_to_lds();
-        const uint64_t word = word_next;
-        __syncthreads();
-        if (tn < t_end) issue_loads(tn); // in flight while this tile is computed
-
-        // ---- S^T = K Q^T : two 32-key blocks x 32 query rows ----------------------------------------------
-        floatx16 acc_s[2];
+    // ---- pieces of the per-tile arithmetic ---------------------------------------------------------------------
+    // K fragment `idx` (= ks*2 + mb) of the first contraction: A operand, 8 channels of one key row per lane
+    auto k_frag = [&](const char *kt, int idx) __attribute__((always_inline)) -> bf16x8 {
+        const int mb = idx & 1, ks = idx >> 1;
+        return *reinterpret_cast<const bf16x8 *>(kt + (mb * 32 + col) * L::kKRowBytes + half * 16 + ks * 32);
+    };
+    // V fragment `idx` (= ks2*MBD + mbd) of the second contraction: A operand, 8 keys of one channel per lane
+    auto v_frag = [&](const char *vt, int idx) __attribute__((always_inline)) -> bf16x8 {
+        const int ks2 = idx / MBD, mbd = idx % MBD;
+        const char *vp = vt + (ks2 * 8 + 4 * half) * L::kVRowBytes + col * 4 + mbd * 128;
+        u32x4 raw;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc_s[mb][j] = 0.f;
-            const char *kp = lds_k + (mb * 32 + col) * L::kKRowBytes + half * 16;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8 *>(kp + ks * 32);
-                acc_s[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], acc_s[mb], 0, 0, 0);
-            }
-        }
-
-        // ---- mask: only draft tiles and the ragged last prefix tile ----------------------------------------
-        // accumulator register i of block mb is key  mb*32 + 16*(i/8) + 8*half + i%8  of the tile
+        for (int jj = 0; jj < 4; ++jj) raw[jj] = *reinterpret_cast<const uint32_t *>(vp + jj * L::kVRowBytes);
+        return __builtin_bit_cast(bf16x8, raw);
+    };
+    // mask of tile `ti` applied to the raw scores: register i of block mb is key mb*32 + 16*(i/8) + 8*half + i%8
+    auto apply_mask = [&](floatx16 (&s)[2], int ti) {
         const bool is_draft = ti >= ntp;
         const int32_t valid = is_draft ? min(kKeysPerTile, n - (ti - ntp) * kKeysPerTile)
                                        : min(kKeysPerTile, P - ti * kKeysPerTile);
-        if (is_draft || valid < kKeysPerTile) {
-            uint64_t vis = is_draft ? word : ~uint64_t(0);
-            if (valid < kKeysPerTile) vis &= (uint64_t(1) << valid) - 1;
-            vis >>= 8 * half;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int key = mb * 32 + 16 * (i / 8) + (i % 8);
-                    if (!((vis >> key) & 1)) acc_s[mb][i] = -__builtin_inff();
-                }
-        }
-
-        // ---- online softmax (per-lane row; the other 16 keys of each block live in lane^32) -----------------
-        float mx = acc_s[0][0];
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc_s[mb][i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        if (__any(m_new > m_run)) {
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e);
-            l_run *= alpha;
-#pragma unroll
-            for (int i = 0; i < MBD; ++i)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc_o[i][j] *= alpha;
-            m_run = m_new;
-        }
-        const float neg_m = -m_run * p.scale_log2e;
-        bf16x8 pf[4];
-        float psum = 0.f;
+        uint64_t vis = is_draft ? mrow[ti - ntp] : ~uint64_t(0);
+        if (valid < kKeysPerTile) vis &= (uint64_t(1) << valid) - 1;
+        vis >>= 8 * half;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const float e = __builtin_amdgcn_exp2f(fmaf(acc_s[mb][i], p.scale_log2e, neg_m));
-                psum += e;
-                pf[mb * 2 + i / 8][i % 8] = (__bf16)e;
+                const int key = mb * 32 + 16 * (i / 8) + (i % 8);
+                if (!((vis >> key) & 1)) s[mb][i] = -__builtin_inff();
             }
-        l_run += psum;
+    };
+    // end of the running-max update for the tile whose in-lane max is mx
+    auto finish_max = [&](float mx) __attribute__((always_inline)) {
+        mx = max_across_halves(mx);
+        const float m_new = fmaxf(m_run, mx);
+        alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e);
+        need_rescale = __any(m_new > m_run);
+        m_run = m_new;
+    };
 
-        // ---- O^T += V^T P^T ---------------------------------------------------------------------------------
+    // ---- the software pipeline ---------------------------------------------------------------------------------
+    // Tiles are taken in order i = 0, 1, ...; at the top of step i
+    //   `s`        raw (masked) scores of tile i, with m_run / alpha already updated for it
+    //   LDS        V(i) in V buffer i&1, K(i+1) in K buffer (i+1)&1
+    //   registers  V(i+1) and K(i+2) on their way in from global memory
+    // Step i:  [rescale acc_o if the max moved]  ->  phase A: scores of tile i+1 on the matrix pipe while the
+    // vector ALU turns `s` into bf16 probabilities  ->  phase B: O^T += V^T P^T on the matrix pipe while the vector
+    // ALU finds the running max of the new scores  ->  one barrier.
+    floatx16 s[2];
+    uint32_t pf[16];           // bf16 probabilities of the tile, two per register, in accumulator-register order
+
+    auto top_of_step = [&](int i, int c1, int c2, int c3) __attribute__((always_inline)) {
+        if (c1 < t_end) store_v((i + 1) & 1);
+        if (c2 < t_end) store_k(i & 1);
+        if (c2 < t_end) load_v(c2);
+        if (c3 < t_end) load_k(c3);
+        l_run *= alpha;
+        if (need_rescale) {
 #pragma unroll
-        for (int ks2 = 0; ks2 < 4; ++ks2) {
-            const char *vp = lds_v + (ks2 * 8 + 4 * half) * L::kVRowBytes + col * 4;
+            for (int x = 0; x < MBD; ++x)
 #pragma unroll
-            for (int mbd = 0; mbd < MBD; ++mbd) {
-                u32x4 raw;
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj)
-                    raw[jj] = *reinterpret_cast<const uint32_t *>(vp + jj * L::kVRowBytes + mbd * 128);
-                const bf16x8 a = __builtin_bit_cast(bf16x8, raw);
-                acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[ks2], acc_o[mbd], 0, 0, 0);
-            }
+                for (int j = 0; j < 16; ++j) acc_o[x][j] *= alpha;
         }
-        ti = tn;
+    };
+
+    // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kt` into s_next.
+    auto phase_a = [&](auto has_next_tag, const char *kt, floatx16 (&s_next)[2]) {
+        constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+        constexpr int PER_SLICE = 32 / NQK;         // scores converted per slice
+        const float neg_m = -m_run * p.scale_log2e;
+        float sum0 = 0.f, sum1 = 0.f;
+        bf16x8 kf[NQK];
+        if (HAS_NEXT) {
+#pragma unroll
+            for (int x = 0; x < 4; ++x) kf[x] = k_frag(kt, x);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) s_next[mb][j] = 0.f;
+        }
+        GSD_SLICE_END();
+#pragma unroll
+        for (int idx = 0; idx < NQK; ++idx) {
+            if (HAS_NEXT) {
+                s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], s_next[idx & 1], 0, 0, 0);
+                if (idx + 4 < NQK) kf[idx + 4] = k_frag(kt, idx + 4);
+            }
+#pragma unroll
+            for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
+                const int e = idx * PER_SLICE + e2;             // linear score index: block e/16, register e%16
+                const float x0 = __builtin_amdgcn_exp2f(fmaf(s[e / 16][e % 16], p.scale_log2e, neg_m));
+                const float x1 = __builtin_amdgcn_exp2f(fmaf(s[(e + 1) / 16][(e + 1) % 16], p.scale_log2e, neg_m));
+                sum0 += x0;
+                sum1 += x1;
+                floatx2 pr;
+                pr[0] = x0;
+                pr[1] = x1;
+                pf[e / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+            }
+            GSD_SLICE_END();
+        }
+        l_run += sum0 + sum1;
+    };
+
+    // phase B.  vt: V buffer of the current tile.  HAS_NEXT: meanwhile reduce the max of s_next (masked if needed).
+    auto phase_b = [&](auto has_next_tag, auto mask_next_tag, const char *vt, floatx16 (&s_next)[2], int next_tile) {
+        constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+        constexpr bool MASK_NEXT = decltype(mask_next_tag)::value;
+        constexpr int PER_SLICE = 32 / NPV;         // scores folded into the max per slice
+        bf16x8 vf[NPV];
+        vf[0] = v_frag(vt, 0);
+        vf[1] = v_frag(vt, 1);
+        if (HAS_NEXT && MASK_NEXT) apply_mask(s_next, next_tile);
+        float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
+        GSD_SLICE_END();
+#pragma unroll
+        for (int idx = 0; idx < NPV; ++idx) {
+            const int ks2 = idx / MBD, mbd = idx % MBD;
+            u32x4 praw;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) praw[x] = pf[4 * ks2 + x];
+            acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, praw), acc_o[mbd], 0, 0, 0);
+            if (idx + 2 < NPV) vf[idx + 2] = v_frag(vt, idx + 2);
+            if (HAS_NEXT) {
+#pragma unroll
+                for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
+                    const int e = idx * PER_SLICE + e2;
+                    if ((e / 2) & 1) mx1 = max3(mx1, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
+                    else mx0 = max3(mx0, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
+                }
+            }
+            GSD_SLICE_END();
+        }
+        if (HAS_NEXT) finish_max(fmaxf(mx0, mx1));
+    };
+
+    using True = std::integral_constant<bool, true>;
+    using False = std::integral_constant<bool, false>;
+
+    int c0 = next_live(t_begin - 1);
+    if (c0 < t_end) {
+        int c1 = next_live(c0), c2 = next_live(c1), c3 = next_live(c2);
+        // prologue: K(0), V(0), K(1) into LDS; scores and max of tile 0; V(1), K(2) in flight
+        load_k(c0);
+        load_v(c0);
+        store_k(0);
+        store_v(0);
+        if (c1 < t_end) {
+            load_k(c1);
+            store_k(1);
+        }
+        __syncthreads();
+        if (c1 < t_end) load_v(c1);
+        if (c2 < t_end) load_k(c2);
+        {
+            const char *kt = lds_k;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) s[mb][j] = 0.f;
+#pragma unroll
+            for (int idx = 0; idx < NQK; ++idx)
+                s[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(kt, idx), qf[idx >> 1], s[idx & 1], 0, 0, 0);
+            if (c0 >= full_end) apply_mask(s, c0);
+            float mx = s[0][0];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[mb][j]);
+            finish_max(mx);
+        }
+        __syncthreads();       // K buffer 0 has been read by every wave before step 0 refills it
+
+        int i = 0;
+        floatx16 s_next[2];
+        auto step = [&](auto mask_next_tag) __attribute__((always_inline)) {
+            top_of_step(i, c1, c2, c3);
+            phase_a(True{}, lds_k + ((i + 1) & 1) * L::kKBytes, s_next);
+            phase_b(True{}, mask_next_tag, lds_v + (i & 1) * L::kVBytes, s_next, c1);
+            __syncthreads();
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) s[mb] = s_next[mb];
+            c0 = c1; c1 = c2; c2 = c3; c3 = next_live(c3);
+            ++i;
+        };
+        while (c1 < full_end) step(False{});      // the next tile is a full prefix tile: no mask code at all
+        while (c1 < t_end) step(True{});          // ragged last prefix tile and draft tiles
+        // last tile: nothing left to prefetch or to score
+        top_of_step(i, t_end, t_end, t_end);
+        phase_a(False{}, nullptr, s_next);
+        phase_b(False{}, False{}, lds_v + (i & 1) * L::kVBytes, s_next, 0);
     }
 
     // ---- epilogue ------------------------------------------------------------------------------------------
