@@ -4,18 +4,26 @@
 // Shape of the work.  All G = Hq/Hkv query heads of a KV head share its K/V rows and (per node) the same mask
 // row, so the (node, head) pairs of one (sequence, KV head) are packed into one row space r = node*G + g and
 // cut into tiles of 128 rows; a work-group of 4 wavefronts owns one tile (32 rows per wave) and walks the KV
-// axis in tiles of 64 keys: first the prefix tiles (no mask code at all, only the ragged last tile is
-// bounded), then the draft tiles, one 64-bit mask word per row per tile; a draft tile whose word is zero for
-// every row of the work-group is skipped outright.
+// axis in tiles of 64 keys: first the prefix tiles (no mask arithmetic, only the ragged last tile is bounded),
+// then the draft tiles, one 64-bit mask word per row per tile; a draft tile whose word is zero for every row
+// of the work-group is skipped outright.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16, fp32 accumulate).  Scores are computed TRANSPOSED,
 // S^T = K . Q^T, so that a lane owns one query row (column n = lane%32) and 16 keys per 32-key block: row
-// max and row sum are in-lane loops plus one exchange with lane^32, and the running rescale factor is a
-// per-lane scalar for the O^T = V^T . P^T accumulators, which have the same column ownership.  The S^T
-// accumulator registers are converted to bf16 in place and fed straight back as the B operand of the second
-// contraction: K rows are stored in LDS in the order that makes each lane's 8 consecutive accumulator
-// registers 8 consecutive keys, and V is stored with adjacent key pairs interleaved per channel so that the
-// A operand of the second contraction is four 32-bit LDS reads per lane.
+// max and row sum are in-lane loops plus one exchange between the wave's halves, and the running rescale
+// factor is a per-lane scalar for the O^T = V^T . P^T accumulators, which have the same column ownership.  The
+// S^T accumulator registers are converted to bf16 in place and fed straight back as the B operand of the
+// second contraction: K rows sit in LDS in the order that makes each lane's 8 consecutive accumulator
+// registers 8 consecutive keys.
+//
+// Data movement.  K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
+// no register staging); both are double-buffered.  Rows keep their 16-byte chunks XOR-swizzled (K by row&7, V
+// by 2*(row&3)) so that the 128-bit K reads and the 64-bit transposing V reads (ds_read_b64_tr_b16, which hands
+// each lane four consecutive keys of one channel from a row-major tile) are free of bank conflicts.
+//
+// Schedule.  The loop is a hand-laid software pipeline: while the matrix pipe computes the scores of tile i+1
+// the vector ALU exponentiates tile i; while the matrix pipe accumulates P.V of tile i the vector ALU reduces
+// the running max of tile i+1.  Two barriers per tile, each followed by the prefetch of the buffer just freed.
 //
 // Small problems are split along the KV axis (gsd_attn_desc.num_splits); a split writes unnormalised fp32
 // partials (O, running max, running sum) and a second kernel merges them in split order.
@@ -64,14 +72,12 @@ struct AttnParams {
 
 template <int D>
 struct Lds {
-    static constexpr int kKRowBytes = D * 2 + 16;                 // padded K row
-    static constexpr int kKBytes = kKeysPerTile * kKRowBytes;
-    static constexpr int kVRowBytes = D * 4;                      // one key PAIR x D channels, 4 bytes each
-    static constexpr int kVBytes = (kKeysPerTile / 2) * kVRowBytes;
-    static constexpr int kTotal = 2 * (kKBytes + kVBytes);        // K and V are both double-buffered
+    static constexpr int kRowBytes = D * 2;                       // one K or V row, unpadded (swizzled instead)
+    static constexpr int kTileBytes = kKeysPerTile * kRowBytes;
+    static constexpr int kTotal = 4 * kTileBytes;                 // K and V, both double-buffered
 };
 
-// position of actual key row r (0..63) inside the LDS K tile: bits 2 and 3 of r swapped (see file comment)
+// position of actual key row r (0..63) inside the LDS K tile: bits 2 and 3 of r swapped (an involution)
 __device__ __forceinline__ int k_lds_row(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
 // Nothing may be moved across this point by the instruction scheduler: the loop body below is laid out by hand
@@ -87,6 +93,22 @@ __device__ __forceinline__ float max_across_halves(float x) {
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// One 16-byte-per-lane global -> LDS copy: lane l's 16 bytes at gbase + voff land at LDS byte lds_base + 16*l.
+// Issued as inline assembly so that the compiler's wait-count pass does not serialise later LDS reads behind
+// it; completion is awaited by hand (dma_wait) before the barrier that publishes the tile.
+__device__ __forceinline__ void dma16(const void *gbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+                 :: "s"(gbase), "v"(voff), "s"(lds_base) : "memory");
+}
+template <int N> __device__ __forceinline__ void dma_wait() {   // at most N vector-memory operations in flight
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const AttnParams p) {
     constexpr int KS = D / 16;          // k-steps of the first contraction
@@ -94,13 +116,13 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     constexpr int NQK = 2 * KS;         // matrix instructions of S^T = K Q^T per tile
     constexpr int NPV = 4 * MBD;        // matrix instructions of O^T += V^T P^T per tile
     constexpr int CHUNKS = D / 8;       // 16-byte chunks per K/V row
-    constexpr int ROWS_PER_PASS = kThreads / CHUNKS;
-    constexpr int K_PASSES = kKeysPerTile / ROWS_PER_PASS;
-    constexpr int V_PASSES = (kKeysPerTile / 2) / ROWS_PER_PASS;
     using L = Lds<D>;
-    __shared__ __attribute__((aligned(16))) char lds[L::kTotal];
-    char *const lds_k = lds;                         // two K tiles
-    char *const lds_v = lds + 2 * L::kKBytes;        // two V tiles
+    constexpr int RB = L::kRowBytes;
+    constexpr int RPI = 1024 / RB;      // tile rows moved by one wave-wide 16-byte-per-lane copy
+    constexpr int IPW = (L::kTileBytes / 1024) / (kThreads / 64);   // such copies per wave per tile
+    __shared__ __attribute__((aligned(1024))) char lds[L::kTotal];
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
+    // buffer x of K at lds + x*kTileBytes, buffer x of V at lds + (2+x)*kTileBytes
 
     // ---- which piece of work: XCD-aware decode of the linear work-group id --------------------------------
     // Hardware deals consecutive work-group ids round-robin to the 8 XCDs; give every XCD a contiguous range
@@ -117,7 +139,7 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5;        // which 8-wide k group / which 4-row group of the accumulator
     const int col = lane & 31;         // query row inside the wave's 32
 
@@ -177,84 +199,83 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     for (int i = 0; i < MBD; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
-    float m_run = kMInit;      // running max of the raw scores, already covering the tile held in `s`
+    float m_run = kMInit;      // running max of the raw scores, already covering the tile whose scores are held
     float l_run = 0.f;         // this lane's share of the running sum (the other half lives in lane^32)
-    float alpha = 1.f;         // pending rescale of acc_o / l_run for the tile held in `s`
+    float alpha = 1.f;         // pending rescale of acc_o / l_run for the tile whose scores are held
     bool need_rescale = false; // wave-uniform: some lane's max moved
 
-    // ---- global -> register -> LDS staging of K/V tiles --------------------------------------------------------
+    // ---- global -> LDS copies of K/V tiles ----------------------------------------------------------------------
+    // Copy j of this wave fills LDS rows (wave*IPW + j)*RPI .. +RPI-1 of the tile buffer; lane l lands in row
+    // +l/CHUNKS, 16-byte slot l%CHUNKS, and therefore fetches the chunk that the swizzle assigns to that slot.
+    static_assert(RPI % 4 == 0 && (RPI == 4 || RPI == 8), "row bookkeeping below assumes 4 or 8 rows per copy");
     const __bf16 *k_seq = p.k + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
     const __bf16 *v_seq = p.v + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
-    const int ld_row = tid / CHUNKS;
-    const int ld_chunk = tid % CHUNKS;
+    const uint32_t row_stride_bytes = uint32_t(p.kv_ts) * 2u;
     const int32_t last_row = P + n - 1;            // last K/V row of the sequence: loads are clamped to it
-    u32x4 kreg[K_PASSES], vreg[2 * V_PASSES];
-
-    auto tile_first_row = [&](int ti) __attribute__((always_inline)) -> int32_t { return ti < ntp ? ti * kKeysPerTile : P + (ti - ntp) * kKeysPerTile; };
-    auto load_k = [&](int ti) __attribute__((always_inline)) {
-        const int32_t r0 = tile_first_row(ti);
+    // Copy j = 0 decides everything: later copies only add compile-time constants (rows) or flip one chunk bit.
+    const int32_t m0 = wave * IPW * RPI + lane / CHUNKS;          // LDS row position filled by copy 0
+    const int slot = lane % CHUNKS;
+    const uint32_t k_src_chunk0 = uint32_t((slot ^ (m0 & 7)) & (CHUNKS - 1)) * 16u;
+    const uint32_t v_src_chunk = uint32_t((slot ^ (2 * (m0 & 3))) & (CHUNKS - 1)) * 16u;   // RPI % 4 == 0
+    auto tile_first_row = [&](int ti) __attribute__((always_inline)) -> int32_t {
+        return ti < ntp ? ti * kKeysPerTile : P + (ti - ntp) * kKeysPerTile;
+    };
+    auto dma_k = [&](int ti, int buf) __attribute__((always_inline)) {
+        const int32_t r0 = tile_first_row(ti) + k_lds_row(m0);
 #pragma unroll
-        for (int ps = 0; ps < K_PASSES; ++ps) {
-            const int32_t r = min(r0 + ps * ROWS_PER_PASS + ld_row, last_row);
-            kreg[ps] = *reinterpret_cast<const u32x4 *>(k_seq + int64_t(r) * p.kv_ts + ld_chunk * 8);
+        for (int j = 0; j < IPW; ++j) {
+            // source row of LDS position m0 + j*RPI: the row permutation is bitwise, and m0, j*RPI share no bits
+            const uint32_t r = uint32_t(min(r0 + k_lds_row(j * RPI), last_row));
+            const uint32_t chunk = k_src_chunk0 ^ uint32_t((((j * RPI) & 7) & (CHUNKS - 1)) * 16);
+            dma16(k_seq, __umul24(r, row_stride_bytes) + chunk,
+                  lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
         }
     };
-    auto load_v = [&](int ti) __attribute__((always_inline)) {
-        const int32_t r0 = tile_first_row(ti);
+    auto dma_v = [&](int ti, int buf) __attribute__((always_inline)) {
+        const int32_t r0 = tile_first_row(ti) + m0;
 #pragma unroll
-        for (int ps = 0; ps < V_PASSES; ++ps) {
-            const int32_t ra = min(r0 + 2 * (ps * ROWS_PER_PASS + ld_row), last_row);
-            const int32_t rb = min(ra + 1, last_row);
-            vreg[2 * ps] = *reinterpret_cast<const u32x4 *>(v_seq + int64_t(ra) * p.kv_ts + ld_chunk * 8);
-            vreg[2 * ps + 1] = *reinterpret_cast<const u32x4 *>(v_seq + int64_t(rb) * p.kv_ts + ld_chunk * 8);
-        }
-    };
-    auto store_k = [&](int buf) __attribute__((always_inline)) {
-        char *base = lds_k + buf * L::kKBytes;
-#pragma unroll
-        for (int ps = 0; ps < K_PASSES; ++ps) {
-            const int r = ps * ROWS_PER_PASS + ld_row;
-            *reinterpret_cast<u32x4 *>(base + k_lds_row(r) * L::kKRowBytes + ld_chunk * 16) = kreg[ps];
-        }
-    };
-    auto store_v = [&](int buf) __attribute__((always_inline)) {
-        char *base = lds_v + buf * L::kVBytes;
-#pragma unroll
-        for (int ps = 0; ps < V_PASSES; ++ps) {
-            const int pr = ps * ROWS_PER_PASS + ld_row;
-            const u32x4 a = vreg[2 * ps], c = vreg[2 * ps + 1];
-            u32x4 lo, hi;   // channel-major pairs: (key 2pr, key 2pr+1) for channels 8*chunk .. +7
-            lo[0] = __builtin_amdgcn_perm(c[0], a[0], 0x05040100u);
-            lo[1] = __builtin_amdgcn_perm(c[0], a[0], 0x07060302u);
-            lo[2] = __builtin_amdgcn_perm(c[1], a[1], 0x05040100u);
-            lo[3] = __builtin_amdgcn_perm(c[1], a[1], 0x07060302u);
-            hi[0] = __builtin_amdgcn_perm(c[2], a[2], 0x05040100u);
-            hi[1] = __builtin_amdgcn_perm(c[2], a[2], 0x07060302u);
-            hi[2] = __builtin_amdgcn_perm(c[3], a[3], 0x05040100u);
-            hi[3] = __builtin_amdgcn_perm(c[3], a[3], 0x07060302u);
-            char *dst = base + pr * L::kVRowBytes + ld_chunk * 32;
-            *reinterpret_cast<u32x4 *>(dst) = lo;
-            *reinterpret_cast<u32x4 *>(dst + 16) = hi;
+        for (int j = 0; j < IPW; ++j) {
+            const uint32_t r = uint32_t(min(r0 + j * RPI, last_row));
+            dma16(v_seq, __umul24(r, row_stride_bytes) + v_src_chunk,
+                  lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
         }
     };
 
-    // ---- pieces of the per-tile arithmetic ---------------------------------------------------------------------
-    // K fragment `idx` (= ks*2 + mb) of the first contraction: A operand, 8 channels of one key row per lane
-    auto k_frag = [&](const char *kt, int idx) __attribute__((always_inline)) -> bf16x8 {
+    // ---- LDS read addresses -------------------------------------------------------------------------------------
+    // K fragment (ks, mb): 16 bytes = channels ks*16 + 8*half .. +7 of LDS row mb*32 + col, i.e. logical chunk
+    // ks*2 + half, found in slot (ks*2 + half) ^ (col & 7).  The XOR never touches bit 3 of the chunk index, so
+    // four per-lane offsets (ks & 3) plus compile-time constants cover all fragments.
+    uint32_t k_off[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) k_off[x] = uint32_t(col * RB + ((((x * 2 + half) ^ (col & 7)) & (CHUNKS - 1)) * 16));
+    // V fragment (ks2, mbd), part h2: transposing 8-byte read.  Within a 16-lane group, lane s supplies the
+    // address of row kv0 + s/4, channels d0 + 4*(s%4) .. +3, and receives keys kv0 .. kv0+3 of channel d0 + s;
+    // d0 = mbd*32 + 16*(group&1), kv0 = ks2*16 + 8*(group>>1) + 4*h2.  Rows are swizzled by 2*(row&3) = 2*(s/4).
+    uint32_t v_off[2];
+    {
+        const int sl = lane & 15, grp = lane >> 4;
+        const int y = (grp & 1) * 2 + (sl & 3) / 2;
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+            v_off[x] = uint32_t((8 * (grp >> 1) + sl / 4) * RB + ((((x * 4 + y) ^ (2 * (sl / 4))) & (CHUNKS - 1)) * 16) +
+                                (sl & 1) * 8);
+    }
+    auto k_frag = [&](int buf, int idx) __attribute__((always_inline)) -> bf16x8 {
         const int mb = idx & 1, ks = idx >> 1;
-        return *reinterpret_cast<const bf16x8 *>(kt + (mb * 32 + col) * L::kKRowBytes + half * 16 + ks * 32);
+        const char *ptr = lds + buf * L::kTileBytes + mb * 32 * RB + (ks >> 2) * 128 + k_off[ks & 3];
+        return *reinterpret_cast<const bf16x8 *>(ptr);
     };
-    // V fragment `idx` (= ks2*MBD + mbd) of the second contraction: A operand, 8 keys of one channel per lane
-    auto v_frag = [&](const char *vt, int idx) __attribute__((always_inline)) -> bf16x8 {
+    auto v_frag = [&](int buf, int idx) __attribute__((always_inline)) -> bf16x8 {
         const int ks2 = idx / MBD, mbd = idx % MBD;
-        const char *vp = vt + (ks2 * 8 + 4 * half) * L::kVRowBytes + col * 4 + mbd * 128;
-        u32x4 raw;
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) raw[jj] = *reinterpret_cast<const uint32_t *>(vp + jj * L::kVRowBytes);
-        return __builtin_bit_cast(bf16x8, raw);
+        const char *ptr = lds + (2 + buf) * L::kTileBytes + ks2 * 16 * RB + (mbd >> 1) * 128 + v_off[mbd & 1];
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (__attribute__((address_space(3))) bf16x4 *)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)ptr);
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (__attribute__((address_space(3))) bf16x4 *)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)(ptr + 4 * RB));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     // mask of tile `ti` applied to the raw scores: register i of block mb is key mb*32 + 16*(i/8) + 8*half + i%8
-    auto apply_mask = [&](floatx16 (&s)[2], int ti) {
+    auto apply_mask = [&](floatx16 (&sc)[2], int ti) __attribute__((always_inline)) {
         const bool is_draft = ti >= ntp;
         const int32_t valid = is_draft ? min(kKeysPerTile, n - (ti - ntp) * kKeysPerTile)
                                        : min(kKeysPerTile, P - ti * kKeysPerTile);
@@ -266,7 +287,7 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int key = mb * 32 + 16 * (i / 8) + (i % 8);
-                if (!((vis >> key) & 1)) s[mb][i] = -__builtin_inff();
+                if (!((vis >> key) & 1)) sc[mb][i] = -__builtin_inff();
             }
     };
     // end of the running-max update for the tile whose in-lane max is mx
@@ -279,21 +300,22 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     };
 
     // ---- the software pipeline ---------------------------------------------------------------------------------
-    // Tiles are taken in order i = 0, 1, ...; at the top of step i
-    //   `s`        raw (masked) scores of tile i, with m_run / alpha already updated for it
-    //   LDS        V(i) in V buffer i&1, K(i+1) in K buffer (i+1)&1
-    //   registers  V(i+1) and K(i+2) on their way in from global memory
-    // Step i:  [rescale acc_o if the max moved]  ->  phase A: scores of tile i+1 on the matrix pipe while the
-    // vector ALU turns `s` into bf16 probabilities  ->  phase B: O^T += V^T P^T on the matrix pipe while the vector
-    // ALU finds the running max of the new scores  ->  one barrier.
-    floatx16 s[2];
-    uint32_t pf[16];           // bf16 probabilities of the tile, two per register, in accumulator-register order
+    // Live tiles are taken in order i = 0, 1, ...; at the top of step i
+    //   registers   raw (masked) scores of tile i, with m_run / alpha already updated for it
+    //   LDS         K(i+1) in K buffer (i+1)&1, complete and published
+    //   in flight   copies issued in the order V(i), K(i+2) -> K buffer i&1, V(i+1) -> V buffer (i+1)&1
+    // Step i:  [rescale acc_o if the max moved]
+    //          phase A: scores of tile i+1 on the matrix pipe while the vector ALU turns the scores of tile i
+    //                   into bf16 probabilities
+    //          wait for V(i)'s copy, barrier, start the copy of K(i+3) into the K buffer just read
+    //          phase B: O^T += V^T P^T on the matrix pipe while the vector ALU reduces the running max of the
+    //                   new scores (masked first if tile i+1 needs it)
+    //          wait for K(i+2)'s copy, barrier, start the copy of V(i+2) into the V buffer just read
+    // Each wait leaves the two younger copies in flight (2*IPW operations); near the end of the range, where
+    // those copies do not exist, it waits for everything.
+    u32x4 pf[4];               // bf16 probabilities of the tile, two per register, in accumulator-register order
 
-    auto top_of_step = [&](int i, int c1, int c2, int c3) __attribute__((always_inline)) {
-        if (c1 < t_end) store_v((i + 1) & 1);
-        if (c2 < t_end) store_k(i & 1);
-        if (c2 < t_end) load_v(c2);
-        if (c3 < t_end) load_k(c3);
+    auto rescale = [&]() __attribute__((always_inline)) {
         l_run *= alpha;
         if (need_rescale) {
 #pragma unroll
@@ -303,8 +325,8 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
         }
     };
 
-    // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kt` into s_next.
-    auto phase_a = [&](auto has_next_tag, const char *kt, floatx16 (&s_next)[2]) {
+    // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next.
+    auto phase_a = [&](auto has_next_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2]) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr int PER_SLICE = 32 / NQK;         // scores converted per slice
         const float neg_m = -m_run * p.scale_log2e;
@@ -312,7 +334,7 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
         bf16x8 kf[NQK];
         if (HAS_NEXT) {
 #pragma unroll
-            for (int x = 0; x < 4; ++x) kf[x] = k_frag(kt, x);
+            for (int x = 0; x < 4; ++x) kf[x] = k_frag(kbuf, x);
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -323,44 +345,45 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
         for (int idx = 0; idx < NQK; ++idx) {
             if (HAS_NEXT) {
                 s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], s_next[idx & 1], 0, 0, 0);
-                if (idx + 4 < NQK) kf[idx + 4] = k_frag(kt, idx + 4);
+                if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
             }
 #pragma unroll
             for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
                 const int e = idx * PER_SLICE + e2;             // linear score index: block e/16, register e%16
-                const float x0 = __builtin_amdgcn_exp2f(fmaf(s[e / 16][e % 16], p.scale_log2e, neg_m));
-                const float x1 = __builtin_amdgcn_exp2f(fmaf(s[(e + 1) / 16][(e + 1) % 16], p.scale_log2e, neg_m));
+                const float x0 = __builtin_amdgcn_exp2f(fmaf(sc[e / 16][e % 16], p.scale_log2e, neg_m));
+                const float x1 = __builtin_amdgcn_exp2f(fmaf(sc[(e + 1) / 16][(e + 1) % 16], p.scale_log2e, neg_m));
                 sum0 += x0;
                 sum1 += x1;
                 floatx2 pr;
                 pr[0] = x0;
                 pr[1] = x1;
-                pf[e / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+                pf[e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
             }
             GSD_SLICE_END();
         }
+        // keep the sums and conversions in this phase: without a use here the compiler sinks them next to their first
+        // use in phase B, behind the barrier, and the overlap with the matrix pipe is lost
+        asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(pf[2]), "+v"(pf[3]), "+v"(sum0), "+v"(sum1));
+        if (HAS_NEXT) asm volatile("" : "+v"(s_next[0]), "+v"(s_next[1]));
         l_run += sum0 + sum1;
     };
 
-    // phase B.  vt: V buffer of the current tile.  HAS_NEXT: meanwhile reduce the max of s_next (masked if needed).
-    auto phase_b = [&](auto has_next_tag, auto mask_next_tag, const char *vt, floatx16 (&s_next)[2], int next_tile) {
+    // phase B.  vbuf: V buffer of the current tile.  HAS_NEXT: meanwhile reduce the max of s_next (masked if
+    // `next_tile` is not a full prefix tile).
+    auto phase_b = [&](auto has_next_tag, int vbuf, floatx16 (&s_next)[2], int next_tile) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
-        constexpr bool MASK_NEXT = decltype(mask_next_tag)::value;
         constexpr int PER_SLICE = 32 / NPV;         // scores folded into the max per slice
         bf16x8 vf[NPV];
-        vf[0] = v_frag(vt, 0);
-        vf[1] = v_frag(vt, 1);
-        if (HAS_NEXT && MASK_NEXT) apply_mask(s_next, next_tile);
+        vf[0] = v_frag(vbuf, 0);
+        vf[1] = v_frag(vbuf, 1);
+        if (HAS_NEXT && next_tile >= full_end) apply_mask(s_next, next_tile);
         float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
         GSD_SLICE_END();
 #pragma unroll
         for (int idx = 0; idx < NPV; ++idx) {
             const int ks2 = idx / MBD, mbd = idx % MBD;
-            u32x4 praw;
-#pragma unroll
-            for (int x = 0; x < 4; ++x) praw[x] = pf[4 * ks2 + x];
-            acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, praw), acc_o[mbd], 0, 0, 0);
-            if (idx + 2 < NPV) vf[idx + 2] = v_frag(vt, idx + 2);
+            acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, pf[ks2]), acc_o[mbd], 0, 0, 0);
+            if (idx + 2 < NPV) vf[idx + 2] = v_frag(vbuf, idx + 2);
             if (HAS_NEXT) {
 #pragma unroll
                 for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
@@ -380,55 +403,70 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     int c0 = next_live(t_begin - 1);
     if (c0 < t_end) {
         int c1 = next_live(c0), c2 = next_live(c1), c3 = next_live(c2);
-        // prologue: K(0), V(0), K(1) into LDS; scores and max of tile 0; V(1), K(2) in flight
-        load_k(c0);
-        load_v(c0);
-        store_k(0);
-        store_v(0);
+        floatx16 sa[2], sb[2];
+        // prologue: K(0), V(0), K(1) on their way; scores and max of tile 0; then V(1), K(2)
+        dma_k(c0, 0);
+        dma_v(c0, 0);
         if (c1 < t_end) {
-            load_k(c1);
-            store_k(1);
+            dma_k(c1, 1);
+            dma_wait<2 * IPW>();
+        } else {
+            dma_wait<0>();
         }
-        __syncthreads();
-        if (c1 < t_end) load_v(c1);
-        if (c2 < t_end) load_k(c2);
+        wg_barrier();
         {
-            const char *kt = lds_k;
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) s[mb][j] = 0.f;
+                for (int j = 0; j < 16; ++j) sa[mb][j] = 0.f;
 #pragma unroll
             for (int idx = 0; idx < NQK; ++idx)
-                s[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(kt, idx), qf[idx >> 1], s[idx & 1], 0, 0, 0);
-            if (c0 >= full_end) apply_mask(s, c0);
-            float mx = s[0][0];
+                sa[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(0, idx), qf[idx >> 1], sa[idx & 1], 0, 0, 0);
+            if (c0 >= full_end) apply_mask(sa, c0);
+            float mx = sa[0][0];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) mx = fmaxf(mx, s[mb][j]);
+                for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sa[mb][j]);
             finish_max(mx);
         }
-        __syncthreads();       // K buffer 0 has been read by every wave before step 0 refills it
+        wg_barrier();          // K buffer 0 has been read by every wave
+        if (c2 < t_end) dma_k(c2, 0);          // same issue order as in the steady state: K(i+2), then V(i+1)
+        if (c1 < t_end) dma_v(c1, 1);
+        if (c2 < t_end) dma_wait<2 * IPW>(); else dma_wait<0>();     // V(0) and K(1) have landed
+        wg_barrier();
 
         int i = 0;
-        floatx16 s_next[2];
-        auto step = [&](auto mask_next_tag) __attribute__((always_inline)) {
-            top_of_step(i, c1, c2, c3);
-            phase_a(True{}, lds_k + ((i + 1) & 1) * L::kKBytes, s_next);
-            phase_b(True{}, mask_next_tag, lds_v + (i & 1) * L::kVBytes, s_next, c1);
-            __syncthreads();
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb) s[mb] = s_next[mb];
+        // one step with the current scores in `cur`, leaving the next tile's scores in `nxt`.  STEADY: tiles
+        // i+2 and i+3 exist, so nothing in the step is conditional and two copies stay in flight at each wait.
+        auto step = [&](auto steady_tag, floatx16 (&cur)[2], floatx16 (&nxt)[2]) __attribute__((always_inline)) {
+            constexpr bool STEADY = decltype(steady_tag)::value;
+            rescale();
+            phase_a(True{}, (i + 1) & 1, cur, nxt);
+            if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // V(i) has landed
+            wg_barrier();
+            if (STEADY || c3 < t_end) dma_k(c3, (i + 1) & 1);
+            phase_b(True{}, i & 1, nxt, c1);
+            if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // K(i+2) has landed
+            wg_barrier();
             c0 = c1; c1 = c2; c2 = c3; c3 = next_live(c3);
+            if (STEADY || c1 < t_end) dma_v(c1, i & 1);                  // V(i+2), now at c1, into the buffer phase B just read
             ++i;
         };
-        while (c1 < full_end) step(False{});      // the next tile is a full prefix tile: no mask code at all
-        while (c1 < t_end) step(True{});          // ragged last prefix tile and draft tiles
+        // steady state, two steps per trip so that the two score buffers swap roles without copies
+        while (c3 < t_end && next_live(c3) < t_end) {
+            step(True{}, sa, sb);
+            step(True{}, sb, sa);
+        }
+        while (c1 < t_end) {
+            step(False{}, sa, sb);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) sa[mb] = sb[mb];
+        }
         // last tile: nothing left to prefetch or to score
-        top_of_step(i, t_end, t_end, t_end);
-        phase_a(False{}, nullptr, s_next);
-        phase_b(False{}, False{}, lds_v + (i & 1) * L::kVBytes, s_next, 0);
+        rescale();
+        phase_a(False{}, 0, sa, sb);
+        phase_b(False{}, i & 1, sb, 0);
     }
 
     // ---- epilogue ------------------------------------------------------------------------------------------

@@ -110,6 +110,13 @@ int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream) {
                         (long long)align);
     if (int64_t(d.total_nodes) * d.num_q_heads > (int64_t(1) << 30))
         return fail(GSD_ERR_UNSUPPORTED, "total_nodes * num_q_heads too large");
+    if (d.dtype == GSD_BF16) {
+        // the bf16 kernel addresses a sequence's K/V rows with 32-bit byte offsets from the sequence's first row
+        const int64_t row_bytes = d.kv_token_stride * 2;
+        if (row_bytes >= (int64_t(1) << 24) ||
+            (int64_t(d.max_prefix) + d.max_nodes) * row_bytes >= (int64_t(1) << 31))
+            return fail(GSD_ERR_UNSUPPORTED, "one sequence's K/V rows span 2 GiB or more (or a row stride >= 16 MiB)");
+    }
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t err;
     if (d.dtype == GSD_F32) {
