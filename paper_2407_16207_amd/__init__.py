@@ -35,7 +35,7 @@ class AttnDesc(ctypes.Structure):
         ("batch", ctypes.c_int32), ("total_nodes", ctypes.c_int32), ("max_nodes", ctypes.c_int32),
         ("max_prefix", ctypes.c_int32), ("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
         ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32), ("words_per_row", ctypes.c_int32),
-        ("num_splits", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32), ("softmax_scale", ctypes.c_float), ("wg_waves", ctypes.c_int32),
         ("q", ctypes.c_void_p), ("o", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("k", ctypes.c_void_p),
         ("v", ctypes.c_void_p), ("kv_offsets", ctypes.c_void_p), ("prefix_lens", ctypes.c_void_p),
         ("node_offsets", ctypes.c_void_p), ("mask", ctypes.c_void_p),
@@ -144,7 +144,8 @@ def gsd_build_mask(node_offsets, parent_offsets, parent_idx, max_nodes: int, wor
 
 
 def make_attn_desc(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_nodes: int, max_prefix: int,
-                   softmax_scale: float, out=None, lse=None, num_splits: int = 0, workspace=None) -> AttnDesc:
+                   softmax_scale: float, out=None, lse=None, num_splits: int = 0, workspace=None,
+                   wg_waves: int = 0) -> AttnDesc:
     import torch
     code = _dtype_code(q)
     for t, name in ((q, "q"), (k, "k"), (v, "v")):
@@ -164,6 +165,7 @@ def make_attn_desc(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_nod
     d.dtype = code
     d.words_per_row = mask.shape[1]
     d.num_splits = int(num_splits)
+    d.wg_waves = int(wg_waves)
     d.softmax_scale = float(softmax_scale)
     d.q, d.k, d.v = q.data_ptr(), k.data_ptr(), v.data_ptr()
     d.o = out.data_ptr() if out is not None else None
@@ -192,7 +194,7 @@ def gsd_dag_attention_splits(desc: AttnDesc) -> int:
 
 def gsd_dag_attention(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_nodes: int, max_prefix: int,
                       softmax_scale: float, out=None, lse=None, num_splits: int = 0, workspace=None, stream=None,
-                      return_lse: bool = False):
+                      return_lse: bool = False, wg_waves: int = 0):
     """DAG-masked attention of every packed node; returns out (same dtype/shape as q).  See gsd.h."""
     import torch
     if out is None:
@@ -202,7 +204,7 @@ def gsd_dag_attention(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_
     if lse is not None:
         _require(lse, torch.float32, "lse")
     desc = make_attn_desc(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_nodes, max_prefix, softmax_scale,
-                          out=out, lse=lse, num_splits=num_splits, workspace=workspace)
+                          out=out, lse=lse, num_splits=num_splits, workspace=workspace, wg_waves=wg_waves)
     if workspace is None:
         need = gsd_dag_attention_workspace(desc)
         if need:

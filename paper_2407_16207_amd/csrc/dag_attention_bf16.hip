@@ -17,8 +17,8 @@
 // registers 8 consecutive keys.
 //
 // Data movement.  K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
-// no register staging); both are double-buffered.  Rows keep their 16-byte chunks XOR-swizzled (K by row&7, V
-// by 2*(row&3)) so that the 128-bit K reads and the 64-bit transposing V reads (ds_read_b64_tr_b16, which hands
+// no register staging); both are double-buffered.  Rows keep their 16-byte chunks XOR-swizzled (K by row%16, V
+// by 4*(row%4) at head_dim 128) so that the 128-bit K reads and the 64-bit transposing V reads (ds_read_b64_tr_b16, which hands
 // each lane four consecutive keys of one channel from a row-major tile) are free of bank conflicts.
 //
 // Schedule.  The loop is a hand-laid software pipeline: while the matrix pipe computes the scores of tile i+1
@@ -42,9 +42,7 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kRowsPerWG = 128;      // query rows (node, head pairs) per work-group
 constexpr int kKeysPerTile = 64;     // keys per KV tile = one mask word
-constexpr int kThreads = 256;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMInit = -1e30f;     // finite stand-in for -inf as the running max
 
@@ -109,8 +107,13 @@ __device__ __forceinline__ void wg_barrier() {
     asm volatile("" ::: "memory");
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const AttnParams p) {
+// NW wavefronts per work-group, 32 query rows each: 8 (256 rows, one work-group per CU) halves the K/V traffic into
+// LDS and the number of copies each wave issues per tile; 4 (128 rows, two work-groups per CU) wastes less when a
+// (sequence, KV head) has few rows.
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(const AttnParams p) {
+    constexpr int kThreads = NW * 64;
+    constexpr int kRowsPerWG = NW * 32;
     constexpr int KS = D / 16;          // k-steps of the first contraction
     constexpr int MBD = D / 32;         // 32-channel blocks of the output
     constexpr int NQK = 2 * KS;         // matrix instructions of S^T = K Q^T per tile
@@ -120,6 +123,8 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     constexpr int RB = L::kRowBytes;
     constexpr int RPI = 1024 / RB;      // tile rows moved by one wave-wide 16-byte-per-lane copy
     constexpr int IPW = (L::kTileBytes / 1024) / (kThreads / 64);   // such copies per wave per tile
+    // K-row swizzle: a bitwise-linear function of the LDS row position (so it distributes over the sums below)
+    auto k_swz = [](int m) __attribute__((always_inline)) -> int { return D == 128 ? (m & 15) : ((m >> 1) & 7); };
     __shared__ __attribute__((aligned(1024))) char lds[L::kTotal];
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)lds;
     // buffer x of K at lds + x*kTileBytes, buffer x of V at lds + (2+x)*kTileBytes
@@ -208,6 +213,7 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     // Copy j of this wave fills LDS rows (wave*IPW + j)*RPI .. +RPI-1 of the tile buffer; lane l lands in row
     // +l/CHUNKS, 16-byte slot l%CHUNKS, and therefore fetches the chunk that the swizzle assigns to that slot.
     static_assert(RPI % 4 == 0 && (RPI == 4 || RPI == 8), "row bookkeeping below assumes 4 or 8 rows per copy");
+    static_assert(IPW >= 1 && IPW * (kThreads / 64) * 1024 == L::kTileBytes, "the waves' copies must tile the buffer");
     const __bf16 *k_seq = p.k + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
     const __bf16 *v_seq = p.v + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
     const uint32_t row_stride_bytes = uint32_t(p.kv_ts) * 2u;
@@ -215,59 +221,65 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     // Copy j = 0 decides everything: later copies only add compile-time constants (rows) or flip one chunk bit.
     const int32_t m0 = wave * IPW * RPI + lane / CHUNKS;          // LDS row position filled by copy 0
     const int slot = lane % CHUNKS;
-    const uint32_t k_src_chunk0 = uint32_t((slot ^ (m0 & 7)) & (CHUNKS - 1)) * 16u;
-    const uint32_t v_src_chunk = uint32_t((slot ^ (2 * (m0 & 3))) & (CHUNKS - 1)) * 16u;   // RPI % 4 == 0
+    const uint32_t k_src_chunk0 = uint32_t(slot ^ k_swz(m0)) * 16u;
+    const uint32_t v_src_chunk = uint32_t((slot ^ ((CHUNKS / 4) * (m0 & 3))) & (CHUNKS - 1)) * 16u;  // RPI % 4 == 0
     auto tile_first_row = [&](int ti) __attribute__((always_inline)) -> int32_t {
         return ti < ntp ? ti * kKeysPerTile : P + (ti - ntp) * kKeysPerTile;
     };
+    // copy j (0..IPW-1) of this wave's share of tile ti into K / V buffer `buf`
+    auto dma_k_one = [&](int ti, int buf, int j) __attribute__((always_inline)) {
+        // source row of LDS position m0 + j*RPI: the row permutation is bitwise, and m0, j*RPI share no bits
+        const uint32_t r = uint32_t(min(tile_first_row(ti) + k_lds_row(m0) + k_lds_row(j * RPI), last_row));
+        const uint32_t chunk = k_src_chunk0 ^ uint32_t(k_swz(j * RPI) * 16);
+        dma16(k_seq, __umul24(r, row_stride_bytes) + chunk, lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
+    };
+    auto dma_v_one = [&](int ti, int buf, int j) __attribute__((always_inline)) {
+        const uint32_t r = uint32_t(min(tile_first_row(ti) + m0 + j * RPI, last_row));
+        dma16(v_seq, __umul24(r, row_stride_bytes) + v_src_chunk,
+              lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
+    };
     auto dma_k = [&](int ti, int buf) __attribute__((always_inline)) {
-        const int32_t r0 = tile_first_row(ti) + k_lds_row(m0);
 #pragma unroll
-        for (int j = 0; j < IPW; ++j) {
-            // source row of LDS position m0 + j*RPI: the row permutation is bitwise, and m0, j*RPI share no bits
-            const uint32_t r = uint32_t(min(r0 + k_lds_row(j * RPI), last_row));
-            const uint32_t chunk = k_src_chunk0 ^ uint32_t((((j * RPI) & 7) & (CHUNKS - 1)) * 16);
-            dma16(k_seq, __umul24(r, row_stride_bytes) + chunk,
-                  lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
-        }
+        for (int j = 0; j < IPW; ++j) dma_k_one(ti, buf, j);
     };
     auto dma_v = [&](int ti, int buf) __attribute__((always_inline)) {
-        const int32_t r0 = tile_first_row(ti) + m0;
 #pragma unroll
-        for (int j = 0; j < IPW; ++j) {
-            const uint32_t r = uint32_t(min(r0 + j * RPI, last_row));
-            dma16(v_seq, __umul24(r, row_stride_bytes) + v_src_chunk,
-                  lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
-        }
+        for (int j = 0; j < IPW; ++j) dma_v_one(ti, buf, j);
     };
 
     // ---- LDS read addresses -------------------------------------------------------------------------------------
+    // The LDS has 64 four-byte banks: a 128-bit read is served 16 lanes at a time, a 64-bit read 32 lanes at a
+    // time, and the lanes served together must not meet in a bank.  Hence the swizzles: a K row at LDS position
+    // m keeps logical 16-byte chunk c in slot c ^ k_swz(m) (16 consecutive rows fill the 16 slots of a 256-byte
+    // bank line exactly once); a V row r keeps chunk c in slot c ^ (CHUNKS/4)*(r % 4).
+    //
     // K fragment (ks, mb): 16 bytes = channels ks*16 + 8*half .. +7 of LDS row mb*32 + col, i.e. logical chunk
-    // ks*2 + half, found in slot (ks*2 + half) ^ (col & 7).  The XOR never touches bit 3 of the chunk index, so
-    // four per-lane offsets (ks & 3) plus compile-time constants cover all fragments.
-    uint32_t k_off[4];
+    // ks*2 + half.  Its byte address is (row base + (half ^ k_swz(col))*16) ^ (ks*32): one per-lane value per ks.
+    uint32_t k_off[KS];
 #pragma unroll
-    for (int x = 0; x < 4; ++x) k_off[x] = uint32_t(col * RB + ((((x * 2 + half) ^ (col & 7)) & (CHUNKS - 1)) * 16));
+    for (int ks = 0; ks < KS; ++ks)
+        k_off[ks] = uint32_t(col * RB + ((half ^ k_swz(col)) * 16)) ^ uint32_t(ks * 32);
     // V fragment (ks2, mbd), part h2: transposing 8-byte read.  Within a 16-lane group, lane s supplies the
     // address of row kv0 + s/4, channels d0 + 4*(s%4) .. +3, and receives keys kv0 .. kv0+3 of channel d0 + s;
-    // d0 = mbd*32 + 16*(group&1), kv0 = ks2*16 + 8*(group>>1) + 4*h2.  Rows are swizzled by 2*(row&3) = 2*(s/4).
-    uint32_t v_off[2];
+    // d0 = mbd*32 + 16*(group&1), kv0 = ks2*16 + 8*(group>>1) + 4*h2, so row % 4 = s/4.  Logical chunk
+    // mbd*4 + y with y = 2*(group&1) + (s%4)/2; its address is (per-lane value) ^ (mbd*64).
+    uint32_t v_off[MBD];
     {
         const int sl = lane & 15, grp = lane >> 4;
         const int y = (grp & 1) * 2 + (sl & 3) / 2;
+        const uint32_t v0 = uint32_t((8 * (grp >> 1) + sl / 4) * RB + (((y ^ ((CHUNKS / 4) * (sl / 4))) & (CHUNKS - 1)) * 16) +
+                                     (sl & 1) * 8);
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
-            v_off[x] = uint32_t((8 * (grp >> 1) + sl / 4) * RB + ((((x * 4 + y) ^ (2 * (sl / 4))) & (CHUNKS - 1)) * 16) +
-                                (sl & 1) * 8);
+        for (int x = 0; x < MBD; ++x) v_off[x] = v0 ^ uint32_t(x * 64);
     }
     auto k_frag = [&](int buf, int idx) __attribute__((always_inline)) -> bf16x8 {
         const int mb = idx & 1, ks = idx >> 1;
-        const char *ptr = lds + buf * L::kTileBytes + mb * 32 * RB + (ks >> 2) * 128 + k_off[ks & 3];
+        const char *ptr = lds + buf * L::kTileBytes + mb * 32 * RB + k_off[ks];
         return *reinterpret_cast<const bf16x8 *>(ptr);
     };
     auto v_frag = [&](int buf, int idx) __attribute__((always_inline)) -> bf16x8 {
         const int ks2 = idx / MBD, mbd = idx % MBD;
-        const char *ptr = lds + (2 + buf) * L::kTileBytes + ks2 * 16 * RB + (mbd >> 1) * 128 + v_off[mbd & 1];
+        const char *ptr = lds + (2 + buf) * L::kTileBytes + ks2 * 16 * RB + v_off[mbd];
         const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
             (__attribute__((address_space(3))) bf16x4 *)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)ptr);
         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
@@ -303,14 +315,14 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     // Live tiles are taken in order i = 0, 1, ...; at the top of step i
     //   registers   raw (masked) scores of tile i, with m_run / alpha already updated for it
     //   LDS         K(i+1) in K buffer (i+1)&1, complete and published
-    //   in flight   copies issued in the order V(i), K(i+2) -> K buffer i&1, V(i+1) -> V buffer (i+1)&1
+    //   in flight   copies issued in the order V(i), K(i+2) -> K buffer i&1 (V(i+1) is issued during phase A)
     // Step i:  [rescale acc_o if the max moved]
     //          phase A: scores of tile i+1 on the matrix pipe while the vector ALU turns the scores of tile i
     //                   into bf16 probabilities
-    //          wait for V(i)'s copy, barrier, start the copy of K(i+3) into the K buffer just read
+    //          wait for V(i)'s copy, barrier (now the K buffer just read may be refilled with K(i+3), in phase B)
     //          phase B: O^T += V^T P^T on the matrix pipe while the vector ALU reduces the running max of the
     //                   new scores (masked first if tile i+1 needs it)
-    //          wait for K(i+2)'s copy, barrier, start the copy of V(i+2) into the V buffer just read
+    //          wait for K(i+2)'s copy, barrier (now the V buffer just read may be refilled, in the next phase A)
     // Each wait leaves the two younger copies in flight (2*IPW operations); near the end of the range, where
     // those copies do not exist, it waits for everything.
     u32x4 pf[4];               // bf16 probabilities of the tile, two per register, in accumulator-register order
@@ -326,7 +338,9 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
     };
 
     // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next.
-    auto phase_a = [&](auto has_next_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2]) __attribute__((always_inline)) {
+    // HAS_NEXT also spreads the copy of the next tile's V (tile `v_tile` into V buffer `v_buf`) over the slices:
+    // issued back to back after a barrier, the copies of all eight waves queue up in the texture path.
+    auto phase_a = [&](auto has_next_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr int PER_SLICE = 32 / NQK;         // scores converted per slice
         const float neg_m = -m_run * p.scale_log2e;
@@ -346,6 +360,7 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
             if (HAS_NEXT) {
                 s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], s_next[idx & 1], 0, 0, 0);
                 if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
+                if (idx % (NQK / IPW) == 1) dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
             }
 #pragma unroll
             for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
@@ -370,12 +385,14 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
 
     // phase B.  vbuf: V buffer of the current tile.  HAS_NEXT: meanwhile reduce the max of s_next (masked if
     // `next_tile` is not a full prefix tile).
-    auto phase_b = [&](auto has_next_tag, int vbuf, floatx16 (&s_next)[2], int next_tile) __attribute__((always_inline)) {
+    // COPY_K spreads the copy of tile `k_tile` into K buffer `k_buf` over the slices.
+    auto phase_b = [&](auto has_next_tag, auto copy_k_tag, int vbuf, floatx16 (&s_next)[2], int next_tile, int k_tile, int k_buf) __attribute__((always_inline)) {
+        constexpr bool COPY_K = decltype(copy_k_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr int PER_SLICE = 32 / NPV;         // scores folded into the max per slice
         bf16x8 vf[NPV];
-        vf[0] = v_frag(vbuf, 0);
-        vf[1] = v_frag(vbuf, 1);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) vf[x] = v_frag(vbuf, x);
         if (HAS_NEXT && next_tile >= full_end) apply_mask(s_next, next_tile);
         float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
         GSD_SLICE_END();
@@ -383,7 +400,8 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
         for (int idx = 0; idx < NPV; ++idx) {
             const int ks2 = idx / MBD, mbd = idx % MBD;
             acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, pf[ks2]), acc_o[mbd], 0, 0, 0);
-            if (idx + 2 < NPV) vf[idx + 2] = v_frag(vbuf, idx + 2);
+            if (idx + 4 < NPV) vf[idx + 4] = v_frag(vbuf, idx + 4);
+            if (COPY_K && idx % (NPV / IPW) == 1) dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
             if (HAS_NEXT) {
 #pragma unroll
                 for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
@@ -431,9 +449,12 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
             finish_max(mx);
         }
         wg_barrier();          // K buffer 0 has been read by every wave
-        if (c2 < t_end) dma_k(c2, 0);          // same issue order as in the steady state: K(i+2), then V(i+1)
-        if (c1 < t_end) dma_v(c1, 1);
-        if (c2 < t_end) dma_wait<2 * IPW>(); else dma_wait<0>();     // V(0) and K(1) have landed
+        if (c2 < t_end) {
+            dma_k(c2, 0);
+            dma_wait<IPW>();   // V(0) and K(1) have landed
+        } else {
+            dma_wait<0>();
+        }
         wg_barrier();
 
         int i = 0;
@@ -442,15 +463,14 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
         auto step = [&](auto steady_tag, floatx16 (&cur)[2], floatx16 (&nxt)[2]) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;
             rescale();
-            phase_a(True{}, (i + 1) & 1, cur, nxt);
+            phase_a(True{}, (i + 1) & 1, cur, nxt, c1, (i + 1) & 1);    // also starts the copy of V(i+1)
             if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // V(i) has landed
             wg_barrier();
-            if (STEADY || c3 < t_end) dma_k(c3, (i + 1) & 1);
-            phase_b(True{}, i & 1, nxt, c1);
+            if (!STEADY && c3 < t_end) dma_k(c3, (i + 1) & 1);
+            phase_b(True{}, steady_tag, i & 1, nxt, c1, c3, (i + 1) & 1);   // steady: also copies K(i+3)
             if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // K(i+2) has landed
             wg_barrier();
             c0 = c1; c1 = c2; c2 = c3; c3 = next_live(c3);
-            if (STEADY || c1 < t_end) dma_v(c1, i & 1);                  // V(i+2), now at c1, into the buffer phase B just read
             ++i;
         };
         // steady state, two steps per trip so that the two score buffers swap roles without copies
@@ -465,8 +485,8 @@ __global__ __launch_bounds__(kThreads, 2) void dag_attention_bf16_kernel(const A
         }
         // last tile: nothing left to prefetch or to score
         rescale();
-        phase_a(False{}, 0, sa, sb);
-        phase_b(False{}, i & 1, sb, 0);
+        phase_a(False{}, 0, sa, sb, 0, 0);
+        phase_b(False{}, False{}, i & 1, sb, 0, 0, 0);
     }
 
     // ---- epilogue ------------------------------------------------------------------------------------------
@@ -543,18 +563,26 @@ __global__ __launch_bounds__(256) void dag_attention_combine_kernel(const AttnPa
 
 // ---------------------------------------------------------------------------------------------- host side
 
+// wavefronts per work-group: 8 (256-row tiles) when a (sequence, KV head) can fill them, else 4
+static int waves_of(const gsd_attn_desc &d) {
+    if (d.wg_waves == 4 || d.wg_waves == 8) return d.wg_waves;
+    const int group = d.num_q_heads / d.num_kv_heads;
+    return d.max_nodes * group >= 256 ? 8 : 4;
+}
+
 static int q_tiles_of(const gsd_attn_desc &d) {
     const int group = d.num_q_heads / d.num_kv_heads;
-    return (d.max_nodes * group + kRowsPerWG - 1) / kRowsPerWG;
+    const int rows_per_wg = waves_of(d) * 32;
+    return (d.max_nodes * group + rows_per_wg - 1) / rows_per_wg;
 }
 
 int attention_bf16_splits(const gsd_attn_desc &d) {
     const int nt_max = (d.max_prefix + kKeysPerTile - 1) / kKeysPerTile + (d.max_nodes + kKeysPerTile - 1) / kKeysPerTile;
     int splits = d.num_splits;
     if (splits <= 0) {
-        // aim for about two work-groups per compute unit; never fewer than 4 KV tiles per split
-        const int64_t base = int64_t(q_tiles_of(d)) * d.batch * d.num_kv_heads;
-        splits = int((512 + base - 1) / base);
+        // aim for sixteen wavefronts per compute unit in total; never fewer than 4 KV tiles per split
+        const int64_t base = int64_t(q_tiles_of(d)) * d.batch * d.num_kv_heads * waves_of(d);
+        splits = int((4096 + base - 1) / base);
         const int cap = nt_max / 4 > 0 ? nt_max / 4 : 1;
         if (splits > cap) splits = cap;
     }
@@ -587,11 +615,16 @@ hipError_t launch_attention_bf16(const gsd_attn_desc &d, int splits, hipStream_t
     p.scale = d.softmax_scale;
     p.scale_log2e = d.softmax_scale * kLog2e;
 
-    const dim3 grid(p.wg_per_xcd * 8), block(kThreads);
-    if (d.head_dim == 128)
-        hipLaunchKernelGGL(dag_attention_bf16_kernel<128>, grid, block, 0, stream, p);
+    const int nw = waves_of(d);
+    const dim3 grid(p.wg_per_xcd * 8), block(nw * 64);
+    if (d.head_dim == 128 && nw == 8)
+        hipLaunchKernelGGL((dag_attention_bf16_kernel<128, 8>), grid, block, 0, stream, p);
+    else if (d.head_dim == 128)
+        hipLaunchKernelGGL((dag_attention_bf16_kernel<128, 4>), grid, block, 0, stream, p);
+    else if (nw == 8)
+        hipLaunchKernelGGL((dag_attention_bf16_kernel<64, 8>), grid, block, 0, stream, p);
     else
-        hipLaunchKernelGGL(dag_attention_bf16_kernel<64>, grid, block, 0, stream, p);
+        hipLaunchKernelGGL((dag_attention_bf16_kernel<64, 4>), grid, block, 0, stream, p);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (splits > 1) {

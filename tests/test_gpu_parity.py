@@ -151,13 +151,15 @@ def test_attention_fp32_general(gpu, ref, D):
     check_attention(gpu, ref, w)
 
 
+@pytest.mark.parametrize("waves", [4, 8])
 @pytest.mark.parametrize("splits", [1, 2, 3, 7])
 @pytest.mark.parametrize("D", [128, 64])
-def test_attention_bf16_small_all_rows(gpu, ref, D, splits):
-    """Several row tiles and KV tiles, ragged tails on both axes, GQA, an empty prefix, forced KV splits."""
+def test_attention_bf16_small_all_rows(gpu, ref, D, splits, waves):
+    """Several row tiles and KV tiles, ragged tails on both axes, GQA, an empty prefix, forced KV splits, both
+    work-group shapes (128- and 256-row tiles)."""
     rng = np.random.default_rng(100 + D + splits)
     w = custom_workload(rng, [200, 1, 65, 37], [333, 0, 64, 130], 8, 2, D, "bf16")
-    check_attention(gpu, ref, w, num_splits=splits)
+    check_attention(gpu, ref, w, num_splits=splits, wg_waves=waves)
 
 
 def test_attention_bf16_mha_and_odd_group(gpu, ref):
@@ -165,6 +167,7 @@ def test_attention_bf16_mha_and_odd_group(gpu, ref):
     check_attention(gpu, ref, custom_workload(rng, [70, 3], [129, 5], 3, 3, 128, "bf16"))     # MHA
     check_attention(gpu, ref, custom_workload(rng, [90, 130], [200, 63], 6, 2, 128, "bf16"))  # group of 3
     check_attention(gpu, ref, custom_workload(rng, [512], [100], 8, 1, 128, "bf16"))          # 4096 rows, 8 words
+    check_attention(gpu, ref, custom_workload(rng, [300, 40], [70, 1000], 4, 4, 128, "bf16"), wg_waves=8)
 
 
 def test_attention_chain_equals_causal_sdpa(gpu):
