@@ -328,7 +328,6 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     u32x4 pf[4];               // bf16 probabilities of the tile, two per register, in accumulator-register order
 
     auto rescale = [&]() __attribute__((always_inline)) {
-        l_run *= alpha;
         if (need_rescale) {
 #pragma unroll
             for (int x = 0; x < MBD; ++x)
@@ -336,15 +335,33 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
                 for (int j = 0; j < 16; ++j) acc_o[x][j] *= alpha;
         }
     };
+    // scores e and e+1 of `sc` -> bf16 probabilities relative to the running max (neg_m = -m_run*scale*log2e), stored
+    // in accumulator-register order; their sum is taken from the ROUNDED pair (one dot-product instruction), so the
+    // normaliser adds up exactly the weights that multiply V.
+    bf16x2 ones2;
+    ones2[0] = (__bf16)1.0f;
+    ones2[1] = (__bf16)1.0f;
+    auto convert_pair = [&](floatx16 (&sc)[2], int e, float neg_m, float &sum) __attribute__((always_inline)) {
+        floatx2 x;
+        x[0] = __builtin_amdgcn_exp2f(fmaf(sc[e / 16][e % 16], p.scale_log2e, neg_m));
+        x[1] = __builtin_amdgcn_exp2f(fmaf(sc[(e + 1) / 16][(e + 1) % 16], p.scale_log2e, neg_m));
+        const bf16x2 pr = __builtin_convertvector(x, bf16x2);
+        pf[e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, pr);
+        sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, sum, false);
+    };
 
-    // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next.
-    // HAS_NEXT also spreads the copy of the next tile's V (tile `v_tile` into V buffer `v_buf`) over the slices:
-    // issued back to back after a barrier, the copies of all eight waves queue up in the texture path.
+    // The exponentials are the vector ALU's heaviest load, so they are split between the two phases: phase B of
+    // step i-1 converts scores 0..15 of tile i (right after it has found the tile's max), phase A of step i
+    // converts scores 16..31.
+    //
+    // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next, and spread
+    // the copy of the next tile's V (tile `v_tile` into V buffer `v_buf`) over the slices: issued back to back after
+    // a barrier, the copies of all the waves queue up in the texture path.
     auto phase_a = [&](auto has_next_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
-        constexpr int PER_SLICE = 32 / NQK;         // scores converted per slice
+        constexpr int EVERY = NQK / 8;              // one pair of scores every EVERY slices
         const float neg_m = -m_run * p.scale_log2e;
-        float sum0 = 0.f, sum1 = 0.f;
+        float sum = 0.f;
         bf16x8 kf[NQK];
         if (HAS_NEXT) {
 #pragma unroll
@@ -362,39 +379,33 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
                 if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
                 if (idx % (NQK / IPW) == 1) dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
             }
-#pragma unroll
-            for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
-                const int e = idx * PER_SLICE + e2;             // linear score index: block e/16, register e%16
-                const float x0 = __builtin_amdgcn_exp2f(fmaf(sc[e / 16][e % 16], p.scale_log2e, neg_m));
-                const float x1 = __builtin_amdgcn_exp2f(fmaf(sc[(e + 1) / 16][(e + 1) % 16], p.scale_log2e, neg_m));
-                sum0 += x0;
-                sum1 += x1;
-                floatx2 pr;
-                pr[0] = x0;
-                pr[1] = x1;
-                pf[e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
-            }
+            if (idx % EVERY == 0) convert_pair(sc, 16 + 2 * (idx / EVERY), neg_m, sum);
             GSD_SLICE_END();
         }
-        // keep the sums and conversions in this phase: without a use here the compiler sinks them next to their first
-        // use in phase B, behind the barrier, and the overlap with the matrix pipe is lost
-        asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(pf[2]), "+v"(pf[3]), "+v"(sum0), "+v"(sum1));
+        // keep the conversions in this phase: without a use here the compiler sinks them next to their first use in
+        // phase B, behind the barrier, and the overlap with the matrix pipe is lost
+        asm volatile("" : "+v"(pf[2]), "+v"(pf[3]), "+v"(sum));
         if (HAS_NEXT) asm volatile("" : "+v"(s_next[0]), "+v"(s_next[1]));
-        l_run += sum0 + sum1;
+        l_run += sum;
     };
 
-    // phase B.  vbuf: V buffer of the current tile.  HAS_NEXT: meanwhile reduce the max of s_next (masked if
-    // `next_tile` is not a full prefix tile).
+    // phase B.  vbuf: V buffer of the current tile.  HAS_NEXT: meanwhile the vector ALU masks s_next if `next_tile`
+    // is not a full prefix tile, reduces its max (first quarter of the slices), updates the running max and the
+    // running sum, and converts scores 0..15 (second half of the slices; pf[0] and pf[1] have been consumed by then).
     // COPY_K spreads the copy of tile `k_tile` into K buffer `k_buf` over the slices.
     auto phase_b = [&](auto has_next_tag, auto copy_k_tag, int vbuf, floatx16 (&s_next)[2], int next_tile, int k_tile, int k_buf) __attribute__((always_inline)) {
         constexpr bool COPY_K = decltype(copy_k_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
-        constexpr int PER_SLICE = 32 / NPV;         // scores folded into the max per slice
+        constexpr int MAX_SLICES = NPV / 4;             // slices that reduce the max
+        constexpr int MAX_PER_SLICE = 16 / MAX_SLICES;  // max3 operations (pairs of scores) in each of them
+        constexpr int CONV_FIRST = NPV / 2;             // first slice that converts
+        constexpr int CONV_PER_SLICE = 8 / (NPV / 2);   // pairs converted per slice
         bf16x8 vf[NPV];
 #pragma unroll
         for (int x = 0; x < 4; ++x) vf[x] = v_frag(vbuf, x);
         if (HAS_NEXT && next_tile >= full_end) apply_mask(s_next, next_tile);
         float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
+        float neg_m = 0.f, sum = 0.f;
         GSD_SLICE_END();
 #pragma unroll
         for (int idx = 0; idx < NPV; ++idx) {
@@ -403,16 +414,31 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             if (idx + 4 < NPV) vf[idx + 4] = v_frag(vbuf, idx + 4);
             if (COPY_K && idx % (NPV / IPW) == 1) dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
             if (HAS_NEXT) {
+                if (idx < MAX_SLICES) {
 #pragma unroll
-                for (int e2 = 0; e2 < PER_SLICE; e2 += 2) {
-                    const int e = idx * PER_SLICE + e2;
-                    if ((e / 2) & 1) mx1 = max3(mx1, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
-                    else mx0 = max3(mx0, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
+                    for (int x = 0; x < MAX_PER_SLICE; ++x) {
+                        const int e = 2 * (idx * MAX_PER_SLICE + x);
+                        if (x & 1) mx1 = max3(mx1, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
+                        else mx0 = max3(mx0, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
+                    }
+                }
+                if (idx == MAX_SLICES) {
+                    finish_max(fmaxf(mx0, mx1));
+                    l_run *= alpha;
+                    neg_m = -m_run * p.scale_log2e;
+                }
+                if (idx >= CONV_FIRST) {
+#pragma unroll
+                    for (int x = 0; x < CONV_PER_SLICE; ++x)
+                        convert_pair(s_next, 2 * ((idx - CONV_FIRST) * CONV_PER_SLICE + x), neg_m, sum);
                 }
             }
             GSD_SLICE_END();
         }
-        if (HAS_NEXT) finish_max(fmaxf(mx0, mx1));
+        if (HAS_NEXT) {
+            asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(sum));
+            l_run += sum;
+        }
     };
 
     using True = std::integral_constant<bool, true>;
@@ -447,6 +473,12 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
 #pragma unroll
                 for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sa[mb][j]);
             finish_max(mx);
+            l_run *= alpha;
+            const float neg_m = -m_run * p.scale_log2e;
+            float sum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; e += 2) convert_pair(sa, e, neg_m, sum);
+            l_run += sum;
         }
         wg_barrier();          // K buffer 0 has been read by every wave
         if (c2 < t_end) {
@@ -460,8 +492,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         int i = 0;
         // one step with the current scores in `cur`, leaving the next tile's scores in `nxt`.  STEADY: tiles
         // i+2 and i+3 exist, so nothing in the step is conditional and two copies stay in flight at each wait.
-        auto step = [&](auto steady_tag, floatx16 (&cur)[2], floatx16 (&nxt)[2]) __attribute__((always_inline)) {
+        // FAST: tile i+4 is known to be the prefix tile right after tile i+3 (no search for the next live tile).
+        auto step = [&](auto steady_tag, auto fast_tag, floatx16 (&cur)[2], floatx16 (&nxt)[2]) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;
+            constexpr bool FAST = decltype(fast_tag)::value;
             rescale();
             phase_a(True{}, (i + 1) & 1, cur, nxt, c1, (i + 1) & 1);    // also starts the copy of V(i+1)
             if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // V(i) has landed
@@ -470,16 +504,22 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             phase_b(True{}, steady_tag, i & 1, nxt, c1, c3, (i + 1) & 1);   // steady: also copies K(i+3)
             if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // K(i+2) has landed
             wg_barrier();
-            c0 = c1; c1 = c2; c2 = c3; c3 = next_live(c3);
+            c0 = c1; c1 = c2; c2 = c3; c3 = FAST ? c3 + 1 : next_live(c3);
             ++i;
         };
-        // steady state, two steps per trip so that the two score buffers swap roles without copies
-        while (c3 < t_end && next_live(c3) < t_end) {
-            step(True{}, sa, sb);
-            step(True{}, sb, sa);
+        // steady state over the prefix, two steps per trip so that the two score buffers swap roles without copies
+        const int pre_end = min(t_end, ntp);
+        while (c3 + 2 < pre_end) {
+            step(True{}, True{}, sa, sb);
+            step(True{}, True{}, sb, sa);
         }
-        while (c1 < t_end) {
-            step(False{}, sa, sb);
+        while (c3 < t_end) {       // the rest of the steady state: the next live tile has to be searched for
+            step(True{}, False{}, sa, sb);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) sa[mb] = sb[mb];
+        }
+        while (c1 < t_end) {       // the last steps: no more tiles to prefetch
+            step(False{}, False{}, sa, sb);
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) sa[mb] = sb[mb];
         }
