@@ -44,7 +44,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kKeysPerTile = 64;     // keys per KV tile = one mask word
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kMInit = -1e30f;     // finite stand-in for -inf as the running max
+constexpr float kMInit = -1e30f;     // finite stand-in for -inf: the offset stored for a partial without any visible key
+constexpr float kLazyMax = 8.0f;     // a row's offset follows its running max only once a score exceeds it by this much (log2)
 
 struct AttnParams {
     const __bf16 *q;
@@ -57,7 +58,7 @@ struct AttnParams {
     const int32_t *node_offsets;
     const uint64_t *mask;
     float *part_o;      // [splits][T][Hq][D] fp32 unnormalised
-    float *part_ml;     // [splits][T][Hq][2]  (running max of raw scores, running sum)
+    float *part_ml;     // [splits][T][Hq][2]  (offset in the log2 domain, sum of 2^(score - offset))
     int64_t q_ts, q_hs, o_ts, o_hs, kv_ts, kv_hs;
     int32_t batch, total_nodes, max_nodes, num_q_heads, num_kv_heads, group, words_per_row;
     int32_t q_tiles;    // row tiles per (sequence, KV head)
@@ -197,6 +198,12 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         const __bf16 *qp = p.q + t * p.q_ts + int64_t(head) * p.q_hs + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+        // Fold softmax_scale*log2(e) into Q once (rounded back to bf16), so that the matrix pipe delivers the
+        // exponent of 2 directly and the vector ALU spends no multiply per score.
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int z = 0; z < 8; ++z) qf[ks][z] = (__bf16)((float)qf[ks][z] * p.scale_log2e);
     }
 
     floatx16 acc_o[MBD];
@@ -204,7 +211,16 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     for (int i = 0; i < MBD; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
-    float m_run = kMInit;      // running max of the raw scores, already covering the tile whose scores are held
+    // Scores leave the matrix pipe already in the exponent's domain and already shifted: the first matrix
+    // instruction of every score block accumulates onto m_vec, sixteen copies of -m_run.  m_run is the row's
+    // offset, not its exact running max: it is raised only when a score exceeds it by more than kLazyMax (softmax
+    // does not care which offset is used, and 2^8 is nowhere near the range of fp32 or bf16), so in the steady
+    // state no rescaling and no per-score subtraction happens at all.
+    float m_run = 0.f;         // offset (log2 domain) applied to the tile whose scores are held
+    bool m_set = false;        // the offset has been taken from real scores (the first visible key sets it)
+    floatx16 m_vec;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) m_vec[j] = 0.f;
     float l_run = 0.f;         // this lane's share of the running sum (the other half lives in lane^32)
     float alpha = 1.f;         // pending rescale of acc_o / l_run for the tile whose scores are held
     bool need_rescale = false; // wave-uniform: some lane's max moved
@@ -303,17 +319,32 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             }
     };
     // end of the running-max update for the tile whose in-lane max is mx
-    auto finish_max = [&](float mx) __attribute__((always_inline)) {
+    // mx: in-lane max of the tile's shifted scores `sc`.  Moves the offset where it has to (rarely), fixing up this
+    // tile's scores, the running sum and m_vec; the accumulators are rescaled by the caller (need_rescale, alpha).
+    auto finish_max = [&](float mx, floatx16 (&sc)[2]) __attribute__((always_inline)) {
         mx = max_across_halves(mx);
-        const float m_new = fmaxf(m_run, mx);
-        alpha = __builtin_amdgcn_exp2f((m_run - m_new) * p.scale_log2e);
-        need_rescale = __any(m_new > m_run);
-        m_run = m_new;
+        const bool seen = mx > -__builtin_inff();
+        const bool grow = seen && (mx > kLazyMax || !m_set);
+        m_set = m_set || seen;
+        need_rescale = __any(grow);
+        alpha = 1.f;
+        if (need_rescale) {
+            const float delta = grow ? mx : 0.f;
+            m_run += delta;
+            alpha = __builtin_amdgcn_exp2f(-delta);
+            l_run *= alpha;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) m_vec[j] = -m_run;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) sc[mb][j] -= delta;
+        }
     };
 
     // ---- the software pipeline ---------------------------------------------------------------------------------
     // Live tiles are taken in order i = 0, 1, ...; at the top of step i
-    //   registers   raw (masked) scores of tile i, with m_run / alpha already updated for it
+    //   registers   shifted (masked) scores of tile i, with m_run / alpha already updated for it
     //   LDS         K(i+1) in K buffer (i+1)&1, complete and published
     //   in flight   copies issued in the order V(i), K(i+2) -> K buffer i&1 (V(i+1) is issued during phase A)
     // Step i:  [rescale acc_o if the max moved]
@@ -335,16 +366,16 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
                 for (int j = 0; j < 16; ++j) acc_o[x][j] *= alpha;
         }
     };
-    // scores e and e+1 of `sc` -> bf16 probabilities relative to the running max (neg_m = -m_run*scale*log2e), stored
+    // scores e and e+1 of `sc` (already shifted exponents of 2) -> bf16 probabilities, stored
     // in accumulator-register order; their sum is taken from the ROUNDED pair (one dot-product instruction), so the
     // normaliser adds up exactly the weights that multiply V.
     bf16x2 ones2;
     ones2[0] = (__bf16)1.0f;
     ones2[1] = (__bf16)1.0f;
-    auto convert_pair = [&](floatx16 (&sc)[2], int e, float neg_m, float &sum) __attribute__((always_inline)) {
+    auto convert_pair = [&](floatx16 (&sc)[2], int e, float &sum) __attribute__((always_inline)) {
         floatx2 x;
-        x[0] = __builtin_amdgcn_exp2f(fmaf(sc[e / 16][e % 16], p.scale_log2e, neg_m));
-        x[1] = __builtin_amdgcn_exp2f(fmaf(sc[(e + 1) / 16][(e + 1) % 16], p.scale_log2e, neg_m));
+        x[0] = __builtin_amdgcn_exp2f(sc[e / 16][e % 16]);
+        x[1] = __builtin_amdgcn_exp2f(sc[(e + 1) / 16][(e + 1) % 16]);
         const bf16x2 pr = __builtin_convertvector(x, bf16x2);
         pf[e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, pr);
         sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, sum, false);
@@ -360,26 +391,21 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     auto phase_a = [&](auto has_next_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr int EVERY = NQK / 8;              // one pair of scores every EVERY slices
-        const float neg_m = -m_run * p.scale_log2e;
         float sum = 0.f;
         bf16x8 kf[NQK];
         if (HAS_NEXT) {
 #pragma unroll
             for (int x = 0; x < 4; ++x) kf[x] = k_frag(kbuf, x);
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) s_next[mb][j] = 0.f;
         }
         GSD_SLICE_END();
 #pragma unroll
         for (int idx = 0; idx < NQK; ++idx) {
             if (HAS_NEXT) {
-                s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], s_next[idx & 1], 0, 0, 0);
+                s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], idx < 2 ? m_vec : s_next[idx & 1], 0, 0, 0);
                 if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
                 if (idx % (NQK / IPW) == 1) dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
             }
-            if (idx % EVERY == 0) convert_pair(sc, 16 + 2 * (idx / EVERY), neg_m, sum);
+            if (idx % EVERY == 0) convert_pair(sc, 16 + 2 * (idx / EVERY), sum);
             GSD_SLICE_END();
         }
         // keep the conversions in this phase: without a use here the compiler sinks them next to their first use in
@@ -405,7 +431,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         for (int x = 0; x < 4; ++x) vf[x] = v_frag(vbuf, x);
         if (HAS_NEXT && next_tile >= full_end) apply_mask(s_next, next_tile);
         float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
-        float neg_m = 0.f, sum = 0.f;
+        float sum = 0.f;
         GSD_SLICE_END();
 #pragma unroll
         for (int idx = 0; idx < NPV; ++idx) {
@@ -422,15 +448,11 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
                         else mx0 = max3(mx0, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
                     }
                 }
-                if (idx == MAX_SLICES) {
-                    finish_max(fmaxf(mx0, mx1));
-                    l_run *= alpha;
-                    neg_m = -m_run * p.scale_log2e;
-                }
+                if (idx == MAX_SLICES) finish_max(fmaxf(mx0, mx1), s_next);
                 if (idx >= CONV_FIRST) {
 #pragma unroll
                     for (int x = 0; x < CONV_PER_SLICE; ++x)
-                        convert_pair(s_next, 2 * ((idx - CONV_FIRST) * CONV_PER_SLICE + x), neg_m, sum);
+                        convert_pair(s_next, 2 * ((idx - CONV_FIRST) * CONV_PER_SLICE + x), sum);
                 }
             }
             GSD_SLICE_END();
@@ -460,24 +482,18 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         wg_barrier();
         {
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) sa[mb][j] = 0.f;
-#pragma unroll
             for (int idx = 0; idx < NQK; ++idx)
-                sa[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(0, idx), qf[idx >> 1], sa[idx & 1], 0, 0, 0);
+                sa[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(0, idx), qf[idx >> 1], idx < 2 ? m_vec : sa[idx & 1], 0, 0, 0);
             if (c0 >= full_end) apply_mask(sa, c0);
             float mx = sa[0][0];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sa[mb][j]);
-            finish_max(mx);
-            l_run *= alpha;
-            const float neg_m = -m_run * p.scale_log2e;
+            finish_max(mx, sa);
             float sum = 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; e += 2) convert_pair(sa, e, neg_m, sum);
+            for (int e = 0; e < 16; e += 2) convert_pair(sa, e, sum);
             l_run += sum;
         }
         wg_barrier();          // K buffer 0 has been read by every wave
@@ -547,7 +563,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             }
         if (p.lse && half == 0)
             p.lse[t * p.num_q_heads + head] =
-                l_tot > 0.f ? m_run * p.scale + __logf(l_tot) : -__builtin_inff();
+                l_tot > 0.f ? (m_run + __log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
     } else {
         const int64_t prow = (int64_t(split) * p.total_nodes + t) * p.num_q_heads + head;
         float *op = p.part_o + prow * D + 4 * half;
@@ -562,7 +578,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             }
         if (half == 0) {
             floatx2 ml;
-            ml[0] = m_run;
+            ml[0] = l_tot > 0.f ? m_run : kMInit;
             ml[1] = l_tot;
             *reinterpret_cast<floatx2 *>(p.part_ml + prow * 2) = ml;
         }
@@ -589,7 +605,7 @@ __global__ __launch_bounds__(256) void dag_attention_combine_kernel(const AttnPa
     for (int s = 0; s < p.splits; ++s) {
         const int64_t prow = int64_t(s) * rows + row;
         const float ms = p.part_ml[prow * 2], ls = p.part_ml[prow * 2 + 1];
-        const float w = __builtin_amdgcn_exp2f((ms - m) * p.scale_log2e);
+        const float w = __builtin_amdgcn_exp2f(ms - m);
         l = fmaf(ls, w, l);
 #pragma unroll
         for (int e = 0; e < PER_LANE; ++e) acc[e] = fmaf(p.part_o[prow * D + lane * PER_LANE + e], w, acc[e]);
@@ -598,7 +614,7 @@ __global__ __launch_bounds__(256) void dag_attention_combine_kernel(const AttnPa
     __bf16 *op = p.o + t * p.o_ts + int64_t(head) * p.o_hs + lane * PER_LANE;
 #pragma unroll
     for (int e = 0; e < PER_LANE; ++e) op[e] = (__bf16)(acc[e] * inv);
-    if (p.lse && lane == 0) p.lse[row] = l > 0.f ? m * p.scale + __logf(l) : -__builtin_inff();
+    if (p.lse && lane == 0) p.lse[row] = l > 0.f ? (m + __log2f(l)) * 0.6931471805599453f : -__builtin_inff();
 }
 
 // ---------------------------------------------------------------------------------------------- host side

@@ -136,7 +136,9 @@ def check_attention(gpu, ref, w, d=None, rows=None, **kw):
     print(f"[attn] {w.cfg.name} {kw} max-abs err {err:.3e} lse err {lse_err:.3e}", flush=True)
     assert np.isfinite(got).all()
     assert err <= tol, err
-    assert lse_err <= (1e-4 if w.cfg.dtype == "f32" else 2e-3), lse_err
+    # the bf16 path folds scale*log2(e) into Q (one more bf16 rounding of Q: relative 2^-9 per element, so a few
+    # 1e-3 on a score) and sums bf16-rounded probabilities; its log-sum-exp is an auxiliary output
+    assert lse_err <= (1e-4 if w.cfg.dtype == "f32" else 1e-2), lse_err
     return out
 
 
