@@ -254,6 +254,23 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         dma16(v_seq, __umul24(r, row_stride_bytes) + v_src_chunk,
               lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
     };
+    // The same copies for a tile whose 64 rows all exist (a full prefix tile): no clamp, the lane's offset is a
+    // constant and the tile's and the copy's share of the address is scalar arithmetic on the base pointer.
+    uint32_t k_lane_off[IPW];
+#pragma unroll
+    for (int j = 0; j < IPW; ++j)
+        k_lane_off[j] = uint32_t(k_lds_row(lane / CHUNKS)) * row_stride_bytes + (k_src_chunk0 ^ uint32_t(k_swz(j * RPI) * 16));
+    const uint32_t v_lane_off = uint32_t(lane / CHUNKS) * row_stride_bytes + v_src_chunk;
+    auto dma_k_one_full = [&](int ti, int buf, int j) __attribute__((always_inline)) {
+        const int32_t row = ti * kKeysPerTile + k_lds_row(wave * IPW * RPI + j * RPI);
+        dma16(reinterpret_cast<const char *>(k_seq) + int64_t(row) * row_stride_bytes, k_lane_off[j],
+              lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
+    };
+    auto dma_v_one_full = [&](int ti, int buf, int j) __attribute__((always_inline)) {
+        const int32_t row = ti * kKeysPerTile + wave * IPW * RPI + j * RPI;
+        dma16(reinterpret_cast<const char *>(v_seq) + int64_t(row) * row_stride_bytes, v_lane_off,
+              lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
+    };
     auto dma_k = [&](int ti, int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < IPW; ++j) dma_k_one(ti, buf, j);
@@ -388,8 +405,9 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next, and spread
     // the copy of the next tile's V (tile `v_tile` into V buffer `v_buf`) over the slices: issued back to back after
     // a barrier, the copies of all the waves queue up in the texture path.
-    auto phase_a = [&](auto has_next_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf) __attribute__((always_inline)) {
+    auto phase_a = [&](auto has_next_tag, auto full_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+        constexpr bool FULL = decltype(full_tag)::value;     // the tile being copied is a full prefix tile
         constexpr int EVERY = NQK / 8;              // one pair of scores every EVERY slices
         float sum = 0.f;
         bf16x8 kf[NQK];
@@ -403,7 +421,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             if (HAS_NEXT) {
                 s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], idx < 2 ? m_vec : s_next[idx & 1], 0, 0, 0);
                 if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
-                if (idx % (NQK / IPW) == 1) dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
+                if (idx % (NQK / IPW) == 1) {
+                    if (FULL) dma_v_one_full(v_tile, v_buf, idx / (NQK / IPW));
+                    else dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
+                }
             }
             if (idx % EVERY == 0) convert_pair(sc, 16 + 2 * (idx / EVERY), sum);
             GSD_SLICE_END();
@@ -419,8 +440,9 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // is not a full prefix tile, reduces its max (first quarter of the slices), updates the running max and the
     // running sum, and converts scores 0..15 (second half of the slices; pf[0] and pf[1] have been consumed by then).
     // COPY_K spreads the copy of tile `k_tile` into K buffer `k_buf` over the slices.
-    auto phase_b = [&](auto has_next_tag, auto copy_k_tag, int vbuf, floatx16 (&s_next)[2], int next_tile, int k_tile, int k_buf) __attribute__((always_inline)) {
+    auto phase_b = [&](auto has_next_tag, auto copy_k_tag, auto full_tag, int vbuf, floatx16 (&s_next)[2], int next_tile, int k_tile, int k_buf) __attribute__((always_inline)) {
         constexpr bool COPY_K = decltype(copy_k_tag)::value;
+        constexpr bool FULL = decltype(full_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr int MAX_SLICES = NPV / 4;             // slices that reduce the max
         constexpr int MAX_PER_SLICE = 16 / MAX_SLICES;  // max3 operations (pairs of scores) in each of them
@@ -438,7 +460,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             const int ks2 = idx / MBD, mbd = idx % MBD;
             acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, pf[ks2]), acc_o[mbd], 0, 0, 0);
             if (idx + 4 < NPV) vf[idx + 4] = v_frag(vbuf, idx + 4);
-            if (COPY_K && idx % (NPV / IPW) == 1) dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
+            if (COPY_K && idx % (NPV / IPW) == 1) {
+                if (FULL) dma_k_one_full(k_tile, k_buf, idx / (NPV / IPW));
+                else dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
+            }
             if (HAS_NEXT) {
                 if (idx < MAX_SLICES) {
 #pragma unroll
@@ -508,24 +533,23 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         int i = 0;
         // one step with the current scores in `cur`, leaving the next tile's scores in `nxt`.  STEADY: tiles
         // i+2 and i+3 exist, so nothing in the step is conditional and two copies stay in flight at each wait.
-        // FAST: tile i+4 is known to be the prefix tile right after tile i+3 (no search for the next live tile).
+        // FAST: all tiles up to i+4 are full prefix tiles: no search for the next live tile, no clamp in the copies.
         auto step = [&](auto steady_tag, auto fast_tag, floatx16 (&cur)[2], floatx16 (&nxt)[2]) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;
             constexpr bool FAST = decltype(fast_tag)::value;
             rescale();
-            phase_a(True{}, (i + 1) & 1, cur, nxt, c1, (i + 1) & 1);    // also starts the copy of V(i+1)
+            phase_a(True{}, fast_tag, (i + 1) & 1, cur, nxt, c1, (i + 1) & 1);    // also starts the copy of V(i+1)
             if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // V(i) has landed
             wg_barrier();
             if (!STEADY && c3 < t_end) dma_k(c3, (i + 1) & 1);
-            phase_b(True{}, steady_tag, i & 1, nxt, c1, c3, (i + 1) & 1);   // steady: also copies K(i+3)
+            phase_b(True{}, steady_tag, fast_tag, i & 1, nxt, c1, c3, (i + 1) & 1);   // steady: also copies K(i+3)
             if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // K(i+2) has landed
             wg_barrier();
             c0 = c1; c1 = c2; c2 = c3; c3 = FAST ? c3 + 1 : next_live(c3);
             ++i;
         };
         // steady state over the prefix, two steps per trip so that the two score buffers swap roles without copies
-        const int pre_end = min(t_end, ntp);
-        while (c3 + 2 < pre_end) {
+        while (c3 + 2 < full_end) {
             step(True{}, True{}, sa, sb);
             step(True{}, True{}, sb, sa);
         }
@@ -541,8 +565,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         }
         // last tile: nothing left to prefetch or to score
         rescale();
-        phase_a(False{}, 0, sa, sb, 0, 0);
-        phase_b(False{}, False{}, i & 1, sb, 0, 0, 0);
+        phase_a(False{}, False{}, 0, sa, sb, 0, 0);
+        phase_b(False{}, False{}, False{}, i & 1, sb, 0, 0, 0);
     }
 
     // ---- epilogue ------------------------------------------------------------------------------------------
