@@ -5,7 +5,7 @@
 //     row[i] <- bit(i) | OR_{p in parents(i)} row[p]
 // for all (node, word) items in parallel until nothing changes.  Nodes are in topological order, so the
 // relaxation reaches its (unique) fixed point after at most depth+1 sweeps; the loop is also hard-bounded by
-// the node count, so every wave leaves the kernel.
+// the node count, so every wave leaves the kernel.  A sweep costs one LDS round trip and one barrier.
 #include "gsd_internal.h"
 
 namespace gsd {
@@ -46,23 +46,69 @@ __global__ __launch_bounds__(kMaskThreads) void build_mask_kernel(
     __syncthreads();
     const int32_t *edges = cached ? edge_cache : (parent_idx + e0);
 
+    // Each thread owns up to kItemsPerThread (node, word) items and keeps the first kRegParents parent ids of
+    // each in registers, so a sweep is a handful of independent LDS reads; convergence is signalled through three
+    // rotating LDS flags (set in sweep s, read after its barrier, cleared during sweep s+1 for sweep s+2).
+    constexpr int kItemsPerThread = (GSD_MAX_NODES_PER_SEQ * 8 + kMaskThreads - 1) / kMaskThreads;   // 4096 words max
+    constexpr int kRegParents = 4;
+    int item_node[kItemsPerThread], item_word[kItemsPerThread], item_deg[kItemsPerThread];
+    int item_par[kItemsPerThread][kRegParents];
+#pragma unroll
+    for (int q = 0; q < kItemsPerThread; ++q) {
+        const int idx = threadIdx.x + q * kMaskThreads;
+        item_node[q] = -1;
+        item_word[q] = 0;
+        item_deg[q] = 0;
+#pragma unroll
+        for (int x = 0; x < kRegParents; ++x) item_par[q][x] = -1;
+        if (idx < items) {
+            const int i = idx / W;
+            item_node[q] = i;
+            item_word[q] = idx - i * W;
+            const int e_lo = off_cache[i], e_hi = off_cache[i + 1];
+            item_deg[q] = e_hi - e_lo;
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) {
+                if (e_lo + x < e_hi) {
+                    const int pp = edges[e_lo + x];
+                    if (pp >= 0 && pp < i) item_par[q][x] = pp;
+                    else if (pp != -1) bad = true;
+                }
+            }
+        }
+    }
+    __shared__ int changed_flag[3];
+    if (threadIdx.x < 3) changed_flag[threadIdx.x] = 0;
+    __syncthreads();
+
     for (int sweep = 0; sweep <= n; ++sweep) {
-        int changed = 0;
-        for (int idx = threadIdx.x; idx < items; idx += kMaskThreads) {
-            const int i = idx / W, w = idx - i * W;
+        bool changed = false;
+#pragma unroll
+        for (int q = 0; q < kItemsPerThread; ++q) {
+            const int i = item_node[q];
+            if (i < 0) continue;
+            const int w = item_word[q];
+            const int idx = i * W + w;
             const uint64_t cur = rows[idx];
             uint64_t acc = cur;
-            for (int e = off_cache[i]; e < off_cache[i + 1]; ++e) {
-                const int p = edges[e];
-                if (p >= 0 && p < i) acc |= rows[p * W + w];
-                else if (p != -1) bad = true;
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x)
+                if (item_par[q][x] >= 0) acc |= rows[item_par[q][x] * W + w];
+            for (int e = off_cache[i] + kRegParents; e < off_cache[i] + item_deg[q]; ++e) {   // rare: more parents
+                const int pp = edges[e];
+                if (pp >= 0 && pp < i) acc |= rows[pp * W + w];
+                else if (pp != -1) bad = true;
             }
             if (acc != cur) {
                 rows[idx] = acc;
-                changed = 1;
+                changed = true;
             }
         }
-        if (!__syncthreads_or(changed)) break;
+        const int slot = sweep % 3;
+        if (changed) changed_flag[slot] = 1;
+        if (threadIdx.x == 0) changed_flag[(sweep + 1) % 3] = 0;
+        __syncthreads();
+        if (changed_flag[slot] == 0) break;       // uniform: everybody reads the same flag after the barrier
     }
 
     uint64_t *out = mask + base * W;
