@@ -31,12 +31,14 @@ def popcount_rows(mask_np):
 
 
 def measured_traffic(cfg_name: str):
-    """HBM bytes per attention launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", "attention_hbm_traffic.json")
+    """HBM bytes per attention launch (read + written) from the committed rocprofv3 counter summary, or None."""
+    import re
+    path = os.path.join(ROOT, "profiles", "dag_attention_bf16_cfg4_hbm_traffic.txt")
     try:
         with open(path) as f:
-            return json.load(f).get(cfg_name, {}).get("traffic_bytes_per_launch")
-    except (OSError, ValueError):
+            m = re.search(r"^traffic_bytes_per_launch\[" + re.escape(cfg_name) + r"\]\s*=\s*(\d+)", f.read(), re.M)
+        return int(m.group(1)) if m else None
+    except OSError:
         return None
 
 
