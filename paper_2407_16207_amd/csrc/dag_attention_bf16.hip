@@ -383,19 +383,18 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
                 for (int j = 0; j < 16; ++j) acc_o[x][j] *= alpha;
         }
     };
-    // scores e and e+1 of `sc` (already shifted exponents of 2) -> bf16 probabilities, stored
-    // in accumulator-register order; their sum is taken from the ROUNDED pair (one dot-product instruction), so the
-    // normaliser adds up exactly the weights that multiply V.
-    bf16x2 ones2;
-    ones2[0] = (__bf16)1.0f;
-    ones2[1] = (__bf16)1.0f;
+    // scores e and e+1 of `sc` (already shifted exponents of 2) -> bf16 probabilities, stored in accumulator-register
+    // order, and added to the lane's running sum.  Plain v_add_f32 on purpose: measured on this chip, ordinary vector
+    // instructions (add, fma, max3, cvt_pk_bf16) issue in the shadow of a running matrix instruction for free and
+    // v_exp_f32 for three quarters, but v_dot2c_f32_bf16 (one instruction per pair) runs on the matrix pipe itself,
+    // takes ~2.5x as long as an add and overlaps with nothing.
     auto convert_pair = [&](floatx16 (&sc)[2], int e, float &sum) __attribute__((always_inline)) {
         floatx2 x;
         x[0] = __builtin_amdgcn_exp2f(sc[e / 16][e % 16]);
         x[1] = __builtin_amdgcn_exp2f(sc[(e + 1) / 16][(e + 1) % 16]);
         const bf16x2 pr = __builtin_convertvector(x, bf16x2);
         pf[e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, pr);
-        sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, sum, false);
+        sum += x[0] + x[1];
     };
 
     // The exponentials are the vector ALU's heaviest load, so they are split between the two phases: phase B of
