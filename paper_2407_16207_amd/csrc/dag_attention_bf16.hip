@@ -176,10 +176,24 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     const int full_end = min(t_end, P / kKeysPerTile);      // tiles below this index need no mask at all
 
     // draft tiles that no row of this work-group can see are skipped: bit j of `live` = tile j has a set bit
+    // The rows' mask words are parked in LDS on the way: fetched from global memory inside the loop they would sit
+    // behind the tile copies in the in-order memory counter and stall the wave for a full memory round trip.
+    constexpr int kMaxWords = GSD_MAX_NODES_PER_SEQ / 64;
+    __shared__ uint64_t mask_lds[kRowsPerWG * kMaxWords];
+    uint64_t *my_mask = mask_lds + (wave * 32 + col) * kMaxWords;      // both halves of the wave write the same words
     uint64_t live = 0;
-    for (int j = 0; j < ntd; ++j) {
-        const uint64_t w = row_valid ? mrow[j] : 0;
-        if (__syncthreads_or(w != 0)) live |= uint64_t(1) << (j & 63);
+    {
+        uint64_t words[kMaxWords];
+#pragma unroll
+        for (int j = 0; j < kMaxWords; ++j) words[j] = (row_valid && j < ntd) ? mrow[j] : 0;
+#pragma unroll
+        for (int j = 0; j < kMaxWords; ++j) my_mask[j] = words[j];
+        for (int j = 0; j < ntd; ++j) {
+            uint64_t w = 0;
+#pragma unroll
+            for (int x = 0; x < kMaxWords; ++x) w = (x == j) ? words[x] : w;
+            if (__syncthreads_or(w != 0)) live |= uint64_t(1) << (j & 63);
+        }
     }
     // smallest live tile index > ti inside the split's range, or t_end
     auto next_live = [&](int ti) __attribute__((always_inline)) -> int {
@@ -324,7 +338,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         const bool is_draft = ti >= ntp;
         const int32_t valid = is_draft ? min(kKeysPerTile, n - (ti - ntp) * kKeysPerTile)
                                        : min(kKeysPerTile, P - ti * kKeysPerTile);
-        uint64_t vis = is_draft ? mrow[ti - ntp] : ~uint64_t(0);
+        uint64_t vis = is_draft ? my_mask[ti - ntp] : ~uint64_t(0);
         if (valid < kKeysPerTile) vis &= (uint64_t(1) << valid) - 1;
         vis >>= 8 * half;
 #pragma unroll
