@@ -172,6 +172,29 @@ def test_attention_bf16_mha_and_odd_group(gpu, ref):
     check_attention(gpu, ref, custom_workload(rng, [300, 40], [70, 1000], 4, 4, 128, "bf16"), wg_waves=8)
 
 
+def test_attention_strided_layouts_and_wide_mask_rows(gpu, ref):
+    """K/V stored head-major ([Hkv, R, D]) and Q/O with padded rows, reached through the descriptor's strides; mask rows
+    wider than the graph needs.  Same numbers as the packed layout, bit for bit."""
+    import paper_2407_16207_amd as gsd
+    rng = np.random.default_rng(31)
+    w = custom_workload(rng, [150, 33], [260, 70], 8, 2, 128, "bf16")
+    d = gpu.DeviceWorkload(w)
+    mask = d.build_mask(words_per_row=5)
+    want = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets,
+                             ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)[0], w.softmax_scale)
+    base = d.attention(mask)
+    assert np.abs(gpu.out_to_f64(base) - want).max() <= 2e-2
+    k_hm = d.k.permute(1, 0, 2).contiguous().permute(1, 0, 2)          # same values, head-major storage
+    v_hm = d.v.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    assert k_hm.stride(1) > k_hm.stride(0)
+    q_pad = torch.zeros((d.q.shape[0], d.q.shape[1], 160), dtype=d.q.dtype, device="cuda")[:, :, :128]
+    q_pad.copy_(d.q)
+    o_pad = torch.zeros_like(q_pad)
+    out = gsd.gsd_dag_attention(q_pad, k_hm, v_hm, d.kv_offsets, d.prefix_lens, d.node_offsets, mask, d.max_nodes,
+                                d.max_prefix, w.softmax_scale, out=o_pad)
+    assert torch.equal(out.contiguous().view(torch.int16), base.view(torch.int16))
+
+
 def test_attention_chain_equals_causal_sdpa(gpu):
     """A chain-shaped graph is plain causal attention: checked against torch's own SDPA on the GPU in fp32."""
     rng = np.random.default_rng(9)
