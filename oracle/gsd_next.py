@@ -1,0 +1,86 @@
+"""CPU oracle of the steps around the verify pass: un-merging the token graph into a token tree (Section 5.4)
+and committing the accepted path to the KV cache (the cache update of Section 6.5).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module; the product path never
+does.  Plain Python / numpy, written from the definitions; it shares nothing with the HIP path.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PATH_COUNT_CAP = 1 << 62      # reported path counts saturate here (the true count can be astronomically large)
+
+
+def unmerge_to_tree(node_offsets, parent_offsets, parent_idx, max_tree_nodes):
+    """Section 5.4: verification reverts the token graph to a tree by un-merging; the successors of a merged
+    node are replicated once per way of reaching them.  The un-merged tree therefore has one node per ROOT PATH
+    of the DAG (a path root -> v1 -> ... -> vm along parent edges); the tree parent of a path is the path without
+    its last node; the tree node carries the token (and all per-node data) of the DAG node it ends at, its ORIGIN.
+
+    Tree nodes are listed in this order (the definition of the output's numbering):
+        paths are compared by the DAG id of their END node first; paths ending at the same node are compared by
+        the position (slot) of their last edge in that node's stored parent list; paths that also share that
+        parent are in the order of their parent paths.
+    A parent path always precedes its extensions (the parent's end node has a smaller id), so the numbering is
+    topological and any prefix of the list is a tree; a sequence's list is cut after `max_tree_nodes` entries.
+
+    Returns (tree_node_offsets[B+1] int32, tree_parent[T'] int32 (sequence-local tree id, -1 = root),
+             tree_origin[T'] int32 (sequence-local DAG id), path_count[B] int64 = min(#root paths, 2^62)).
+    """
+    node_offsets = np.asarray(node_offsets, dtype=np.int64)
+    parent_offsets = np.asarray(parent_offsets, dtype=np.int64)
+    parent_idx = np.asarray(parent_idx, dtype=np.int64)
+    B = len(node_offsets) - 1
+    offs = [0]
+    all_parent, all_origin, counts = [], [], []
+    for b in range(B):
+        lo, hi = int(node_offsets[b]), int(node_offsets[b + 1])
+        # replicas[i] = tree ids of the paths ending at DAG node i, in order (only those inside the cut are kept)
+        replicas = [[] for _ in range(hi - lo)]
+        n_paths = [0] * (hi - lo)                        # exact, unbounded Python integers
+        tree_parent, tree_origin = [], []
+        for i in range(hi - lo):
+            for e in range(int(parent_offsets[lo + i]), int(parent_offsets[lo + i + 1])):
+                p = int(parent_idx[e])
+                if p == -1:
+                    n_paths[i] += 1
+                    parent_paths = [-1]
+                else:
+                    assert 0 <= p < i, "parents must be earlier nodes"
+                    n_paths[i] += n_paths[p]
+                    parent_paths = replicas[p]
+                for t in parent_paths:
+                    if len(tree_parent) < max_tree_nodes:
+                        replicas[i].append(len(tree_parent))
+                        tree_parent.append(t)
+                        tree_origin.append(i)
+        total = sum(n_paths)
+        # a path inside the cut has its parent path inside the cut: nothing may be lost before the cut is reached
+        assert len(tree_parent) == min(total, max_tree_nodes)
+        counts.append(min(total, PATH_COUNT_CAP))
+        all_parent.extend(tree_parent)
+        all_origin.extend(tree_origin)
+        offs.append(len(all_parent))
+    return (np.asarray(offs, dtype=np.int32), np.asarray(all_parent, dtype=np.int32),
+            np.asarray(all_origin, dtype=np.int32), np.asarray(counts, dtype=np.int64))
+
+
+def commit_kv(k, v, kv_offsets, prefix_lens, accept_len, accept_path):
+    """Cache update after acceptance (Section 6.5 attributes the "Others" time to it): the accepted tokens become
+    part of the context, everything else drafted in this iteration is dropped.  With a sequence's rows laid out
+    as [prefix rows ; draft rows], the new context of sequence b is
+        old prefix rows, then the rows of accept_path[b][0 .. accept_len[b]) in path order.
+    k, v: [L, R, ...] arrays (L layers, R rows, anything after); returns (new_k, new_v, new_prefix_lens) where
+    rows beyond a sequence's new prefix keep their old contents (they are no longer part of anything)."""
+    k = np.asarray(k)
+    v = np.asarray(v)
+    new_k, new_v = k.copy(), v.copy()
+    new_len = np.asarray(prefix_lens, dtype=np.int32).copy()
+    for b in range(len(prefix_lens)):
+        base = int(kv_offsets[b]) + int(prefix_lens[b])
+        for j in range(int(accept_len[b])):
+            src = base + int(accept_path[b][j])
+            new_k[:, base + j] = k[:, src]
+            new_v[:, base + j] = v[:, src]
+        new_len[b] += int(accept_len[b])
+    return new_k, new_v, new_len

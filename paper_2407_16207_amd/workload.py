@@ -245,3 +245,45 @@ def random_dag(rng: np.random.Generator, n: int, max_parents: int = 3, p_root: f
         parents.extend(ps)
         offsets.append(len(parents))
     return np.asarray(offsets, dtype=np.int32), np.asarray(parents, dtype=np.int32)
+
+
+def merged_tree_dag(rng: np.random.Generator, n: int, max_children: int = 3, n_merges: int = 4):
+    """A token graph shaped like the paper's (Section 5.3): a random token tree of n nodes (every node hangs off
+    the root or an earlier node that still has fewer than max_children children, so ids are topological), in
+    which n_merges leaves R are then "merged" into an earlier-explored node F: R becomes an extra parent of every
+    child of F, which is the edge the paper draws from a redundant node to the first occurrence of its n-gram.
+    Returns CSR (offsets, parents) with each node's parents sorted; -1 = root."""
+    parent = np.full(n, -1, dtype=np.int64)
+    n_children = np.zeros(n + 1, dtype=np.int64)           # slot n counts the root's children
+    for i in range(n):
+        while True:
+            p = int(rng.integers(-1, i))
+            if n_children[p] < max_children or p == -1:
+                break
+        parent[i] = p
+        n_children[p] += 1
+    children = [[] for _ in range(n)]
+    for i in range(n):
+        if parent[i] >= 0:
+            children[int(parent[i])].append(i)
+    plists = [[int(parent[i])] for i in range(n)]
+    leaves = [i for i in range(n) if not children[i]]
+    inner = [i for i in range(n) if children[i]]
+    used = set()
+    for _ in range(n_merges):
+        if not inner:
+            break
+        f = inner[int(rng.integers(0, len(inner)))]
+        cand = [r for r in leaves if r < children[f][0] and r != f and r not in used]
+        if not cand:
+            continue
+        r = cand[int(rng.integers(0, len(cand)))]
+        used.add(r)
+        for c in children[f]:
+            plists[c].append(r)
+    offsets = [0]
+    flat: list[int] = []
+    for i in range(n):
+        flat.extend(sorted(set(plists[i])))
+        offsets.append(len(flat))
+    return np.asarray(offsets, dtype=np.int32), np.asarray(flat, dtype=np.int32)

@@ -1,0 +1,193 @@
+"""Pins for the oracle's un-merge-to-tree step (Section 5.4) and KV-cache commit (Section 6.5)."""
+import numpy as np
+import pytest
+
+from oracle import gsd_next
+from paper_2407_16207_amd.workload import merged_tree_dag, random_dag
+from helpers import all_root_paths, brute_force_accept, chain_dag, kary_tree, mask_to_bool, parents_of
+
+
+def unmerge_one(off, par, cap=1 << 20):
+    n = len(off) - 1
+    o, tp, to, cnt = gsd_next.unmerge_to_tree([0, n], off, par, cap)
+    assert o[0] == 0 and o[1] == len(tp) == len(to)
+    return tp, to, int(cnt[0])
+
+
+def tree_paths(tp, to):
+    """Root path (as DAG ids) of every tree node, following tree parents."""
+    paths = []
+    for t in range(len(tp)):
+        p, cur = [], t
+        while cur != -1:
+            p.append(int(to[cur]))
+            cur = int(tp[cur])
+        paths.append(tuple(reversed(p)))
+    return paths
+
+
+def diamond_chain(k):
+    """k diamonds in a row: node 0; then for each diamond two middle nodes and a join.  2^k root paths to the end."""
+    off, par = [0, 1], [-1]
+    last = 0
+    for _ in range(k):
+        a = len(off) - 1
+        par += [last]; off.append(len(par))        # a
+        par += [last]; off.append(len(par))        # a + 1
+        par += [a, a + 1]; off.append(len(par))    # join
+        last = a + 2
+    return np.asarray(off, dtype=np.int32), np.asarray(par, dtype=np.int32)
+
+
+# ------------------------------------------------------------------------------------------------ un-merge
+def test_hand_diamond():
+    # 0 <- root; 1, 2 <- 0; 3 <- {1, 2} (merged); 4 <- 3.  Un-merging replicates 3 and its successor 4.
+    off = np.array([0, 1, 2, 3, 5, 6], dtype=np.int32)
+    par = np.array([-1, 0, 0, 1, 2, 3], dtype=np.int32)
+    tp, to, cnt = unmerge_one(off, par)
+    assert cnt == 7
+    assert to.tolist() == [0, 1, 2, 3, 3, 4, 4]
+    assert tp.tolist() == [-1, 0, 0, 1, 2, 3, 4]
+
+
+@pytest.mark.parametrize("shape", [("chain", 9), ("tree", (3, 3)), ("tree", (2, 5))])
+def test_tree_is_left_unchanged(shape):
+    off, par = chain_dag(shape[1]) if shape[0] == "chain" else kary_tree(*shape[1])
+    tp, to, cnt = unmerge_one(off, par)
+    n = len(off) - 1
+    assert cnt == n and to.tolist() == list(range(n)) and tp.tolist() == par.tolist()
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_one_tree_node_per_root_path_in_the_defined_order(seed):
+    rng = np.random.default_rng(500 + seed)
+    n = int(rng.integers(1, 13))
+    off, par = random_dag(rng, n, max_parents=3, p_root=0.3) if seed % 2 else merged_tree_dag(rng, n, 3, 3)
+    tp, to, cnt = unmerge_one(off, par)
+    got = tree_paths(tp, to)
+    want = all_root_paths(n, off, par)                      # independent enumeration (walks child lists)
+    assert len(got) == len(set(got)) == len(want) == cnt and set(got) == set(want)
+    # count by linear algebra: c = r + A c  (A[i, p] = 1 per edge p -> i, r[i] = 1 per root edge)
+    A = np.zeros((n, n))
+    r = np.zeros(n)
+    for i in range(n):
+        for p in parents_of(off, par, i):
+            if p == -1:
+                r[i] += 1
+            else:
+                A[i, p] += 1
+    assert cnt == int(round(np.linalg.solve(np.eye(n) - A, r).sum()))
+
+    # order: end node, then slot of the last edge, then (recursively) the parent path
+    def key(path):
+        k = []
+        for j in range(len(path) - 1, -1, -1):
+            prev = path[j - 1] if j else -1
+            k += [path[j], parents_of(off, par, path[j]).index(prev)]
+        return k
+    assert got == sorted(want, key=key)
+    # parents come first, so every prefix is a tree
+    assert all(tp[t] < t for t in range(len(tp)))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_cut_keeps_a_prefix_and_reports_the_full_count(seed):
+    rng = np.random.default_rng(900 + seed)
+    off, par = random_dag(rng, 14, max_parents=3, p_root=0.2)
+    tp, to, cnt = unmerge_one(off, par)
+    for cap in (1, 5, cnt // 2 + 1, cnt, cnt + 3):
+        tpc, toc, cntc = unmerge_one(off, par, cap)
+        k = min(cap, cnt)
+        assert cntc == cnt and tpc.tolist() == tp[:k].tolist() and toc.tolist() == to[:k].tolist()
+
+
+def test_count_saturates():
+    off, par = diamond_chain(70)                            # 2^70 paths end at the last join alone
+    tp, to, cnt = unmerge_one(off, par, cap=300)
+    assert cnt == 1 << 62 and len(tp) == 300
+    off, par = diamond_chain(10)
+    # 1 + sum_{d=1..10} (2^(d-1) + 2^(d-1) + 2^d) = 1 + 4*(2^10 - 1)
+    assert unmerge_one(off, par, cap=16)[2] == 1 + 4 * (2 ** 10 - 1)
+
+
+def test_several_sequences_are_independent():
+    rng = np.random.default_rng(3)
+    dags = [random_dag(rng, n, 3, 0.3) for n in (5, 1, 9)]
+    node_offsets, poff, pidx = [0], [0], []
+    for off, par in dags:
+        node_offsets.append(node_offsets[-1] + len(off) - 1)
+        poff += [int(x) + len(pidx) for x in off[1:]]
+        pidx += par.tolist()
+    o, tp, to, cnt = gsd_next.unmerge_to_tree(node_offsets, poff, pidx, 8)
+    for b, (off, par) in enumerate(dags):
+        tpb, tob, cntb = unmerge_one(off, par, 8)
+        assert tp[o[b]:o[b + 1]].tolist() == tpb.tolist() and to[o[b]:o[b + 1]].tolist() == tob.tolist()
+        assert cnt[b] == cntb
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_verifying_the_tree_accepts_the_same_path(ref, seed):
+    """Acceptance depends only on tokens and predictions along a path, and the tree has exactly the DAG's root
+    paths: the longest accepted path of the un-merged tree, mapped back through `origin`, is the DAG's."""
+    rng = np.random.default_rng(7000 + seed)
+    n = int(rng.integers(1, 15))
+    off, par = random_dag(rng, n, max_parents=3, p_root=0.3)
+    vocab = int(rng.integers(2, 5))
+    tokens = rng.integers(0, vocab, n).astype(np.int32)
+    pred = rng.integers(0, vocab, n).astype(np.int32)
+    root_pred = int(rng.integers(0, vocab))
+    tp, to, cnt = unmerge_one(off, par)
+    m = len(tp)
+    ln, path, bonus = ref.accept_longest_path([0, m], np.arange(m + 1), tp, tokens[to], pred[to], [root_pred])
+    tree_path = [int(to[t]) for t in path[0, :ln[0]]]
+    want_path, want_bonus = brute_force_accept(n, off, par, tokens, pred, root_pred)
+    assert tree_path == want_path and int(bonus[0]) == want_bonus
+    dl, dpath, dbonus = ref.accept_longest_path([0, n], off, par, tokens, pred, [root_pred])
+    assert dpath[0, :dl[0]].tolist() == tree_path and dbonus[0] == bonus[0]
+
+
+def test_tree_mask_rows_are_single_paths(ref):
+    rng = np.random.default_rng(11)
+    off, par = merged_tree_dag(rng, 40, 3, 5)
+    tp, to, cnt = unmerge_one(off, par)
+    m = len(tp)
+    assert m > 40                                            # the merges did replicate something
+    mask, flag = ref.build_mask([0, m], np.arange(m + 1), tp)
+    vis = mask_to_bool(mask, m)
+    paths = tree_paths(tp, to)
+    for t in range(m):
+        assert sorted(int(to[j]) for j in np.flatnonzero(vis[t])) == sorted(paths[t])
+        assert vis[t].sum() == len(paths[t])
+
+
+# ------------------------------------------------------------------------------------------------ KV commit
+def make_cache(rng, layers, prefix_lens, n_draft, width=6):
+    rows = int(sum(p + n_draft for p in prefix_lens))
+    kv_offsets = np.concatenate([[0], np.cumsum([p + n_draft for p in prefix_lens])[:-1]]).astype(np.int64)
+    k = rng.integers(0, 1 << 16, size=(layers, rows, width)).astype(np.uint16)
+    v = rng.integers(0, 1 << 16, size=(layers, rows, width)).astype(np.uint16)
+    return k, v, kv_offsets
+
+
+def test_commit_equals_appending_only_the_accepted_tokens():
+    rng = np.random.default_rng(5)
+    prefix_lens = np.array([7, 0, 3], dtype=np.int32)
+    n_draft = 10
+    k, v, kv_offsets = make_cache(rng, 3, prefix_lens, n_draft)
+    accept_len = np.array([4, 0, 10], dtype=np.int32)
+    accept_path = np.full((3, n_draft), -1, dtype=np.int32)
+    accept_path[0, :4] = [1, 2, 3, 9]                       # row j is overwritten while row path[j'] = j is a source
+    accept_path[2, :] = np.arange(10)                       # a fully accepted chain: nothing moves
+    nk, nv, nl = gsd_next.commit_kv(k, v, kv_offsets, prefix_lens, accept_len, accept_path)
+    assert nl.tolist() == [11, 0, 13]
+    for b in range(3):
+        base = int(kv_offsets[b])
+        P = int(prefix_lens[b])
+        for old, new in ((k, nk), (v, nv)):
+            ctx = np.concatenate([old[:, base:base + P]] +
+                                 [old[:, base + P + a:base + P + a + 1] for a in accept_path[b, :accept_len[b]]], axis=1)
+            assert np.array_equal(new[:, base:base + nl[b]], ctx)
+            # rows past the new context are untouched
+            assert np.array_equal(new[:, base + nl[b]:base + P + n_draft], old[:, base + nl[b]:base + P + n_draft])
+    assert np.array_equal(nk[:, kv_offsets[1]:kv_offsets[2]], k[:, kv_offsets[1]:kv_offsets[2]])
+    assert np.array_equal(nk[:, kv_offsets[2]:], k[:, kv_offsets[2]:])      # identity path: no change at all
