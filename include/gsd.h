@@ -8,6 +8,9 @@
  *   gsd_dag_attention         masked attention of every packed draft node over [context ; visible nodes]
  *   gsd_node_argmax           the verifier's own next token after every node (row argmax of the logits)
  *   gsd_accept_longest_path   longest root path on which every drafted token equals the verifier's choice
+ * and, around that pass,
+ *   gsd_unmerge_to_tree       token graph -> token tree with replicated successors (Section 5.4), gsd_gather_rows
+ *   gsd_commit_kv             accepted path -> contiguous context rows of the KV cache (Section 6.5)
  *
  * Conventions common to all calls
  *   - Every data pointer is a DEVICE pointer owned by the caller; scalars and the descriptor struct are host
@@ -160,6 +163,66 @@ int gsd_accept_longest_path(int32_t batch, int32_t total_nodes, int32_t max_node
                             const void *logits, int dtype, int32_t vocab, int64_t row_stride, int32_t *pred,
                             const int32_t *root_pred, int32_t *accept_len, int32_t *accept_path,
                             int32_t *bonus_token, void *hip_stream);
+
+/*
+ * Un-merging the token graph into a token tree (Section 5.4: before verification the graph is reverted to a
+ * tree; the successors of a merged node are replicated).  The un-merged tree has one node per ROOT PATH of the
+ * graph (root -> v1 -> ... -> vm along parent edges); the tree parent of a path is the path without its last
+ * node, and the tree node stands for the graph node the path ends at (its ORIGIN: same token, same per-node
+ * data).  Tree nodes of a sequence are numbered in this order: by origin id; paths with the same origin by the
+ * position of their last edge in the origin's stored parent list; paths that also share that parent in the
+ * order of their parent paths.  Parents precede children, so the output is itself a valid input of every call
+ * in this header, and so is any prefix of it: a sequence's list is cut after max_tree_nodes entries (the number
+ * of root paths can be exponential in the depth).
+ *
+ *   batch, max_nodes, node_offsets, parent_offsets, parent_idx: the graph, as for gsd_build_mask
+ *   max_tree_nodes      cap on tree nodes per sequence, >= 1, batch * max_tree_nodes < 2^31
+ *   tree_node_offsets   [B+1] int32 out: packed tree nodes of sequence b are rows [b] .. [b+1]-1
+ *   tree_parent         [>= B*max_tree_nodes] int32 out: sequence-local TREE id of the parent, -1 = root.
+ *                       Every tree node has one parent, so the tree's CSR parent_offsets are 0,1,2,...
+ *   tree_parent_offsets [>= B*max_tree_nodes + 1] int32 out or NULL: those CSR offsets (entry g = g, g <= T')
+ *   tree_origin         [>= B*max_tree_nodes] int32 out: sequence-local graph id of the node replicated
+ *   path_count          [B] int64 out: number of root paths of sequence b = its tree size without the cap,
+ *                       saturating at 2^62
+ *   dag_error_flag      as for gsd_build_mask (a malformed edge is ignored)
+ * Only entries below tree_node_offsets[B] are written.  Two launches on `hip_stream`; no host synchronisation:
+ * read tree_node_offsets back to learn T' before sizing the calls that consume the tree.
+ */
+int gsd_unmerge_to_tree(int32_t batch, int32_t max_nodes, int32_t max_tree_nodes, const int32_t *node_offsets,
+                        const int32_t *parent_offsets, const int32_t *parent_idx, int32_t *tree_node_offsets,
+                        int32_t *tree_parent, int32_t *tree_parent_offsets, int32_t *tree_origin,
+                        int64_t *path_count, int32_t *dag_error_flag, void *hip_stream);
+
+/*
+ * Row gather, dst[r] = src[index[r]] for r < rows: carries per-node data (queries, keys, values, tokens,
+ * predictions) from graph nodes to their replicas in the un-merged tree (Section 5.4).
+ *   row_bytes multiple of 4; src/dst strides in bytes, multiples of 4 and >= row_bytes; index [rows] int32,
+ *   each in [0, src_rows) (an index outside that range leaves the destination row untouched).
+ *   src and dst must not overlap.
+ */
+int gsd_gather_rows(int64_t rows, int64_t row_bytes, const void *src, int64_t src_rows, int64_t src_stride_bytes,
+                    const int32_t *index, void *dst, int64_t dst_stride_bytes, void *hip_stream);
+
+/*
+ * KV-cache commit after acceptance (Section 6.5 finds the cache update to be a cost of its own next to drafting
+ * and verifying).  The accepted draft tokens become context, everything else drafted in this iteration is
+ * dropped: for every layer l, for K and for V, and every j < accept_len[b]
+ *     row (kv_offsets[b] + P_b + j)  <-  row (kv_offsets[b] + P_b + accept_path[b][j])        (P_b = prefix_lens[b])
+ * in place, reading every source row before any row that overwrites it, and new_prefix_lens[b] = P_b +
+ * accept_len[b].  Rows past the new prefix keep whatever they held.  accept_path must be what
+ * gsd_accept_longest_path returns (ids strictly increasing, so accept_path[b][j] >= j); an id outside
+ * [j, max_nodes) skips that row.
+ *
+ *   num_layers >= 1; layer l of K starts at (char*)k + l*layer_stride_bytes (same for v)
+ *   row_bytes          bytes of one token's K (or V) in one layer (all KV heads), multiple of 16
+ *   token_stride_bytes distance between consecutive rows, multiple of 16, >= row_bytes
+ *   k, v               16-byte aligned device pointers
+ *   accept_path        [B][max_nodes] int32;  new_prefix_lens [B] int32, must not alias prefix_lens
+ */
+int gsd_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers, int64_t row_bytes, void *k, void *v,
+                  int64_t token_stride_bytes, int64_t layer_stride_bytes, const int64_t *kv_offsets,
+                  const int32_t *prefix_lens, const int32_t *accept_len, const int32_t *accept_path,
+                  int32_t *new_prefix_lens, void *hip_stream);
 
 #ifdef __cplusplus
 }

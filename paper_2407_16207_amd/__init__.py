@@ -2,7 +2,8 @@
 Speculative Decoding.  Argument marshalling only: torch supplies device memory and the stream, every step of
 the path runs in the library's HIP kernels.  There is no CPU fallback; a missing library raises.
 
-    gsd_build_mask, gsd_dag_attention, gsd_node_argmax, gsd_accept_longest_path
+    gsd_build_mask, gsd_dag_attention, gsd_node_argmax, gsd_accept_longest_path,
+    gsd_unmerge_to_tree, gsd_gather_rows, gsd_commit_kv
 
 mirror the C entry points of the same names.
 """
@@ -20,7 +21,8 @@ GSD_F32, GSD_BF16 = 0, 1
 GSD_MAX_NODES_PER_SEQ = 512
 
 EXPORTS = ("gsd_status_string", "gsd_last_error", "gsd_version", "gsd_build_mask", "gsd_dag_attention_workspace",
-           "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_node_argmax", "gsd_accept_longest_path")
+           "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_node_argmax", "gsd_accept_longest_path",
+           "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv")
 
 
 class GsdError(RuntimeError):
@@ -82,6 +84,9 @@ def load_library() -> ctypes.CDLL:
         lib.gsd_node_argmax.argtypes = [i32, i32, ctypes.c_int, vp, i64, vp, vp]
         lib.gsd_accept_longest_path.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_int, i32, i64, vp, vp,
                                                 vp, vp, vp, vp]
+        lib.gsd_unmerge_to_tree.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        lib.gsd_gather_rows.argtypes = [i64, i64, vp, i64, i64, vp, vp, i64, vp]
+        lib.gsd_commit_kv.argtypes = [i32, i32, i32, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -266,3 +271,77 @@ def gsd_accept_longest_path(node_offsets, parent_offsets, parent_idx, tokens, ro
                                                   _ptr(pred), _ptr(root_pred), _ptr(accept_len), _ptr(accept_path),
                                                   _ptr(bonus_token), _stream_ptr(stream)))
     return accept_len, accept_path, bonus_token, pred
+
+
+def gsd_unmerge_to_tree(node_offsets, parent_offsets, parent_idx, max_nodes: int, max_tree_nodes: int,
+                        dag_error_flag=None, stream=None):
+    """Token graph -> token tree with replicated successors.  Returns (tree_node_offsets[B+1], tree_parent,
+    tree_parent_offsets, tree_origin, path_count[B]); the three per-node arrays are allocated at their bound
+    B*max_tree_nodes (+1) and only their first tree_node_offsets[B] (+1) entries are written.  See gsd.h."""
+    import torch
+    for t, name in ((node_offsets, "node_offsets"), (parent_offsets, "parent_offsets"), (parent_idx, "parent_idx")):
+        _require(t, torch.int32, name)
+    batch = node_offsets.numel() - 1
+    dev = node_offsets.device
+    bound = batch * int(max_tree_nodes)
+    tree_node_offsets = torch.empty(batch + 1, dtype=torch.int32, device=dev)
+    tree_parent = torch.empty(bound, dtype=torch.int32, device=dev)
+    tree_parent_offsets = torch.empty(bound + 1, dtype=torch.int32, device=dev)
+    tree_origin = torch.empty(bound, dtype=torch.int32, device=dev)
+    path_count = torch.empty(batch, dtype=torch.int64, device=dev)
+    if dag_error_flag is not None:
+        _require(dag_error_flag, torch.int32, "dag_error_flag")
+    _check(load_library().gsd_unmerge_to_tree(batch, max_nodes, max_tree_nodes, _ptr(node_offsets),
+                                              _ptr(parent_offsets), _ptr(parent_idx), _ptr(tree_node_offsets),
+                                              _ptr(tree_parent), _ptr(tree_parent_offsets), _ptr(tree_origin),
+                                              _ptr(path_count), _ptr(dag_error_flag), _stream_ptr(stream)))
+    return tree_node_offsets, tree_parent, tree_parent_offsets, tree_origin, path_count
+
+
+def gsd_gather_rows(src, index, out=None, rows: int | None = None, stream=None):
+    """out[r] = src[index[r]] along dim 0 (rows of any trailing shape, contiguous within a row).  See gsd.h."""
+    import torch
+    _require(index, torch.int32, "index")
+    if not src.is_cuda or src.dim() < 1 or not src[0].is_contiguous():
+        raise ValueError("src must be a GPU tensor whose rows (dim 0 slices) are contiguous")
+    rows = index.numel() if rows is None else int(rows)
+    if out is None:
+        out = torch.empty((rows,) + tuple(src.shape[1:]), dtype=src.dtype, device=src.device)
+    elif out.dtype != src.dtype or tuple(out.shape[1:]) != tuple(src.shape[1:]) or out.shape[0] < rows or \
+            not out[0].is_contiguous():
+        raise ValueError("out must match src's dtype and row shape and hold `rows` rows")
+    if rows == 0:
+        return out
+    es = src.element_size()
+    row_elems = 1
+    for d in src.shape[1:]:
+        row_elems *= d
+    src_stride = src.stride(0) if src.shape[0] > 1 else row_elems
+    out_stride = out.stride(0) if out.shape[0] > 1 else row_elems
+    _check(load_library().gsd_gather_rows(rows, row_elems * es, _ptr(src), src.shape[0], src_stride * es, _ptr(index),
+                                          _ptr(out), out_stride * es, _stream_ptr(stream)))
+    return out
+
+
+def gsd_commit_kv(k, v, kv_offsets, prefix_lens, accept_len, accept_path, new_prefix_lens=None, stream=None):
+    """In-place KV-cache commit of the accepted path.  k, v: [L, R, Hkv, D] (or [R, Hkv, D] for one layer) with
+    contiguous rows; returns new_prefix_lens[B].  See gsd_commit_kv in gsd.h."""
+    import torch
+    if k.dim() == 3:
+        k, v = k.unsqueeze(0), v.unsqueeze(0)
+    if k.dim() != 4 or k.shape != v.shape or k.stride() != v.stride() or not k.is_cuda or not k[0, 0].is_contiguous():
+        raise ValueError("k and v must be GPU tensors [layers, rows, kv_heads, head_dim] with contiguous rows")
+    _require(kv_offsets, torch.int64, "kv_offsets")
+    for t, name in ((prefix_lens, "prefix_lens"), (accept_len, "accept_len"), (accept_path, "accept_path")):
+        _require(t, torch.int32, name)
+    batch = prefix_lens.numel()
+    max_nodes = accept_path.shape[1]
+    if new_prefix_lens is None:
+        new_prefix_lens = torch.empty(batch, dtype=torch.int32, device=k.device)
+    _require(new_prefix_lens, torch.int32, "new_prefix_lens")
+    es = k.element_size()
+    _check(load_library().gsd_commit_kv(batch, max_nodes, k.shape[0], k.shape[2] * k.shape[3] * es, _ptr(k), _ptr(v),
+                                        k.stride(1) * es, k.stride(0) * es, _ptr(kv_offsets), _ptr(prefix_lens),
+                                        _ptr(accept_len), _ptr(accept_path), _ptr(new_prefix_lens),
+                                        _stream_ptr(stream)))
+    return new_prefix_lens

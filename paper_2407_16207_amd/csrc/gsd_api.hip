@@ -169,4 +169,64 @@ int gsd_accept_longest_path(int32_t batch, int32_t total_nodes, int32_t max_node
     return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_accept_longest_path launch");
 }
 
+int gsd_unmerge_to_tree(int32_t batch, int32_t max_nodes, int32_t max_tree_nodes, const int32_t *node_offsets,
+                        const int32_t *parent_offsets, const int32_t *parent_idx, int32_t *tree_node_offsets,
+                        int32_t *tree_parent, int32_t *tree_parent_offsets, int32_t *tree_origin,
+                        int64_t *path_count, int32_t *dag_error_flag, void *hip_stream) {
+    if (batch < 1 || max_nodes < 1 || max_tree_nodes < 1)
+        return fail(GSD_ERR_INVALID_ARG, "batch, max_nodes and max_tree_nodes must be >= 1");
+    if (max_nodes > GSD_MAX_NODES_PER_SEQ)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", max_nodes, GSD_MAX_NODES_PER_SEQ);
+    if (int64_t(batch) * max_tree_nodes >= (int64_t(1) << 31))
+        return fail(GSD_ERR_UNSUPPORTED, "batch * max_tree_nodes must stay below 2^31");
+    if (!node_offsets || !parent_offsets || !parent_idx || !tree_node_offsets || !tree_parent || !tree_origin ||
+        !path_count)
+        return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    hipError_t err = gsd::launch_unmerge(batch, max_nodes, max_tree_nodes, node_offsets, parent_offsets, parent_idx,
+                                         tree_node_offsets, tree_parent, tree_parent_offsets, tree_origin,
+                                         path_count, dag_error_flag, (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_unmerge_to_tree launch");
+}
+
+int gsd_gather_rows(int64_t rows, int64_t row_bytes, const void *src, int64_t src_rows, int64_t src_stride_bytes,
+                    const int32_t *index, void *dst, int64_t dst_stride_bytes, void *hip_stream) {
+    if (rows < 1 || src_rows < 1 || row_bytes < 4)
+        return fail(GSD_ERR_INVALID_ARG, "rows and src_rows must be >= 1 and row_bytes >= 4");
+    if (row_bytes % 4 != 0 || src_stride_bytes % 4 != 0 || dst_stride_bytes % 4 != 0)
+        return fail(GSD_ERR_INVALID_ARG, "row_bytes and strides must be multiples of 4");
+    if (src_stride_bytes < row_bytes || dst_stride_bytes < row_bytes)
+        return fail(GSD_ERR_INVALID_ARG, "strides must be >= row_bytes");
+    if (row_bytes / 4 > INT32_MAX) return fail(GSD_ERR_UNSUPPORTED, "row_bytes too large");
+    if (!src || !dst || !index) return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    if (reinterpret_cast<uintptr_t>(src) % 4 != 0 || reinterpret_cast<uintptr_t>(dst) % 4 != 0)
+        return fail(GSD_ERR_INVALID_ARG, "src and dst must be 4-byte aligned");
+    hipError_t err = gsd::launch_gather_rows(rows, row_bytes, src, src_rows, src_stride_bytes, index, dst,
+                                             dst_stride_bytes, (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_gather_rows launch");
+}
+
+int gsd_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers, int64_t row_bytes, void *k, void *v,
+                  int64_t token_stride_bytes, int64_t layer_stride_bytes, const int64_t *kv_offsets,
+                  const int32_t *prefix_lens, const int32_t *accept_len, const int32_t *accept_path,
+                  int32_t *new_prefix_lens, void *hip_stream) {
+    if (batch < 1 || max_nodes < 1 || num_layers < 1)
+        return fail(GSD_ERR_INVALID_ARG, "batch, max_nodes and num_layers must be >= 1");
+    if (batch > 32767 || num_layers > 65535)
+        return fail(GSD_ERR_UNSUPPORTED, "batch <= 32767 and num_layers <= 65535 (grid limits)");
+    if (row_bytes < 16 || row_bytes % 16 != 0 || token_stride_bytes % 16 != 0 || token_stride_bytes < row_bytes)
+        return fail(GSD_ERR_INVALID_ARG, "row_bytes and token_stride_bytes must be multiples of 16, stride >= row");
+    if (row_bytes / 16 > INT32_MAX) return fail(GSD_ERR_UNSUPPORTED, "row_bytes too large");
+    if (num_layers > 1 && (layer_stride_bytes % 16 != 0 || layer_stride_bytes < token_stride_bytes))
+        return fail(GSD_ERR_INVALID_ARG, "layer_stride_bytes must be a multiple of 16 and >= token_stride_bytes");
+    if (!k || !v || !kv_offsets || !prefix_lens || !accept_len || !accept_path || !new_prefix_lens)
+        return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    if (!aligned16(k) || !aligned16(v)) return fail(GSD_ERR_INVALID_ARG, "k and v must be 16-byte aligned");
+    if (new_prefix_lens == prefix_lens)
+        return fail(GSD_ERR_INVALID_ARG, "new_prefix_lens must not alias prefix_lens");
+    hipError_t err = gsd::launch_commit_kv(batch, max_nodes, num_layers, row_bytes, k, v, token_stride_bytes,
+                                           layer_stride_bytes, kv_offsets, prefix_lens, accept_len, accept_path,
+                                           new_prefix_lens, (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_commit_kv launch");
+}
+
 }  // extern "C"

@@ -27,4 +27,18 @@ int attention_bf16_splits(const gsd_attn_desc &d);
 size_t attention_bf16_workspace(const gsd_attn_desc &d, int splits);
 hipError_t launch_attention_bf16(const gsd_attn_desc &d, int splits, hipStream_t stream);
 
+hipError_t launch_unmerge(int32_t batch, int32_t max_nodes, int32_t max_tree_nodes, const int32_t *node_offsets,
+                          const int32_t *parent_offsets, const int32_t *parent_idx, int32_t *tree_node_offsets,
+                          int32_t *tree_parent, int32_t *tree_parent_offsets, int32_t *tree_origin,
+                          int64_t *path_count, int32_t *dag_error_flag, hipStream_t stream);
+
+hipError_t launch_gather_rows(int64_t rows, int64_t row_bytes, const void *src, int64_t src_rows,
+                              int64_t src_stride, const int32_t *index, void *dst, int64_t dst_stride,
+                              hipStream_t stream);
+
+hipError_t launch_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers, int64_t row_bytes, void *k, void *v,
+                            int64_t token_stride, int64_t layer_stride, const int64_t *kv_offsets,
+                            const int32_t *prefix_lens, const int32_t *accept_len, const int32_t *accept_path,
+                            int32_t *new_prefix_lens, hipStream_t stream);
+
 }  // namespace gsd

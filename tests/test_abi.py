@@ -105,3 +105,30 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(gsd, "LIB_PATH", "/nonexistent/libgsd.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         gsd.load_library()
+
+
+def test_unmerge_gather_commit_validate(lib):
+    p = ctypes.c_void_p(0x10000)
+    q = ctypes.c_void_p(0x20000)
+    null = ctypes.c_void_p(0)
+    good = [2, 64, 128, p, p, p, p, p, null, p, p, null, null]
+    for pos, value, code in ((0, 0, gsd.GSD_ERR_INVALID_ARG), (1, 513, gsd.GSD_ERR_UNSUPPORTED),
+                             (2, 0, gsd.GSD_ERR_INVALID_ARG), (2, 1 << 30, gsd.GSD_ERR_UNSUPPORTED),
+                             (6, null, gsd.GSD_ERR_INVALID_ARG), (10, null, gsd.GSD_ERR_INVALID_ARG)):
+        bad = list(good)
+        bad[pos] = value
+        assert lib.gsd_unmerge_to_tree(*bad) == code, pos
+    good = [10, 64, p, 100, 64, p, q, 64, null]
+    for pos, value in ((0, 0), (1, 6), (1, 2), (4, 60), (7, 32), (2, null), (5, null), (6, ctypes.c_void_p(0x20002))):
+        bad = list(good)
+        bad[pos] = value
+        assert lib.gsd_gather_rows(*bad) == gsd.GSD_ERR_INVALID_ARG, pos
+    good = [2, 64, 4, 2048, p, q, 2048, 1 << 20, p, p, p, p, q, null]
+    for pos, value, code in ((0, 0, gsd.GSD_ERR_INVALID_ARG), (2, 0, gsd.GSD_ERR_INVALID_ARG),
+                             (2, 70000, gsd.GSD_ERR_UNSUPPORTED), (3, 2040, gsd.GSD_ERR_INVALID_ARG),
+                             (6, 1024, gsd.GSD_ERR_INVALID_ARG), (7, 1000, gsd.GSD_ERR_INVALID_ARG),
+                             (4, ctypes.c_void_p(0x10008), gsd.GSD_ERR_INVALID_ARG), (12, p, gsd.GSD_ERR_INVALID_ARG),
+                             (11, null, gsd.GSD_ERR_INVALID_ARG)):
+        bad = list(good)
+        bad[pos] = value
+        assert lib.gsd_commit_kv(*bad) == code, pos

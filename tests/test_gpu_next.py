@@ -1,0 +1,196 @@
+"""GPU parity for the steps around the verify pass: un-merge-to-tree (Section 5.4) and the KV-cache commit
+(Section 6.5), through the C ABI, bit-exact against the CPU oracle; and the tree variant of the whole verify
+pass against the oracle run on the oracle's tree."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gsd_next
+from paper_2407_16207_amd.workload import make_workload, merged_tree_dag, random_dag, VerifyConfig
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import gpu_util
+    return gpu_util
+
+
+def pack(dags):
+    node_offsets, poff, pidx = [0], [0], []
+    for off, par in dags:
+        node_offsets.append(node_offsets[-1] + len(off) - 1)
+        poff += [int(x) + len(pidx) for x in off[1:]]
+        pidx += par.tolist()
+    return (np.asarray(node_offsets, dtype=np.int32), np.asarray(poff, dtype=np.int32),
+            np.asarray(pidx if pidx else [0], dtype=np.int32))
+
+
+def run_unmerge(gpu, gsd, node_offsets, poff, pidx, max_nodes, cap):
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    o, tp, tpo, to, cnt = gsd.gsd_unmerge_to_tree(gpu.to_dev(node_offsets), gpu.to_dev(poff), gpu.to_dev(pidx),
+                                                  max_nodes, cap, dag_error_flag=flag)
+    torch.cuda.synchronize()
+    o = o.cpu().numpy()
+    total = int(o[-1])
+    return o, tp.cpu().numpy()[:total], tpo.cpu().numpy()[:total + 1], to.cpu().numpy()[:total], \
+        cnt.cpu().numpy(), int(flag.item())
+
+
+def diamond_chain(k):
+    off, par, last = [0, 1], [-1], 0
+    for _ in range(k):
+        a = len(off) - 1
+        par += [last]; off.append(len(par))
+        par += [last]; off.append(len(par))
+        par += [a, a + 1]; off.append(len(par))
+        last = a + 2
+    return np.asarray(off, dtype=np.int32), np.asarray(par, dtype=np.int32)
+
+
+@pytest.mark.parametrize("cap", [1, 7, 64, 512, 4096])
+def test_unmerge_matches_oracle(gpu, cap):
+    import paper_2407_16207_amd as gsd
+    rng = np.random.default_rng(77)
+    dags = [merged_tree_dag(rng, 64, 3, 6), random_dag(rng, 17, 3, 0.3), merged_tree_dag(rng, 1, 3, 0),
+            random_dag(rng, 300, 2, 0.05), diamond_chain(70), merged_tree_dag(rng, 512, 4, 40),
+            (np.array([0, 1, 1, 2], dtype=np.int32), np.array([-1, 0], dtype=np.int32))]   # node 1 has no parent
+    node_offsets, poff, pidx = pack(dags)
+    o, tp, tpo, to, cnt, flag = run_unmerge(gpu, gsd, node_offsets, poff, pidx, 512, cap)
+    ro, rtp, rto, rcnt = gsd_next.unmerge_to_tree(node_offsets, poff, pidx, cap)
+    assert flag == 0
+    assert np.array_equal(o, ro) and np.array_equal(cnt, rcnt)
+    assert np.array_equal(tp, rtp) and np.array_equal(to, rto)
+    assert np.array_equal(tpo, np.arange(len(tp) + 1))
+    assert cnt[4] == 1 << 62                                     # the diamond chain saturates the count
+
+
+def test_unmerge_config_workloads_and_bad_edges(gpu):
+    import paper_2407_16207_amd as gsd
+    for cfg in (1, 3, 5):
+        w = make_workload(cfg, with_logits=False, with_qkv=False)
+        o, tp, tpo, to, cnt, flag = run_unmerge(gpu, gsd, w.node_offsets, w.parent_offsets, w.parent_idx,
+                                                w.max_nodes, 512)
+        ro, rtp, rto, rcnt = gsd_next.unmerge_to_tree(w.node_offsets, w.parent_offsets, w.parent_idx, 512)
+        assert flag == 0 and np.array_equal(o, ro) and np.array_equal(cnt, rcnt)
+        assert np.array_equal(tp, rtp) and np.array_equal(to, rto)
+    # a forward edge and an out-of-range id are ignored and flagged; the rest is as if they were absent
+    off = np.array([0, 1, 3, 5], dtype=np.int32)
+    par = np.array([-1, 0, 2, 1, -7], dtype=np.int32)
+    o, tp, tpo, to, cnt, flag = run_unmerge(gpu, gsd, np.array([0, 3], dtype=np.int32), off, par, 3, 64)
+    assert flag == 1 and to.tolist() == [0, 1, 2] and tp.tolist() == [-1, 0, 1] and cnt.tolist() == [3]
+
+
+def test_gather_rows(gpu):
+    import paper_2407_16207_amd as gsd
+    rng = np.random.default_rng(5)
+    idx = rng.integers(0, 1000, 3001).astype(np.int32)
+    for shape, dtype in (((1000, 8, 128), np.int16), ((1000,), np.int32), ((1000, 3), np.float32),
+                         ((1000, 6), np.int16)):
+        src = rng.integers(-30000, 30000, size=shape).astype(dtype)
+        out = gsd.gsd_gather_rows(torch.from_numpy(src).cuda(), torch.from_numpy(idx).cuda())
+        assert np.array_equal(out.cpu().numpy(), src[idx])
+    # strided source rows (a column slice), and indices out of range leave their rows alone
+    src = rng.integers(0, 100, size=(50, 16)).astype(np.int32)
+    view = torch.from_numpy(src).cuda()[:, 4:12]
+    out = torch.full((6, 8), -5, dtype=torch.int32, device="cuda")
+    gsd.gsd_gather_rows(view, torch.tensor([3, -1, 49, 50, 0, 7], dtype=torch.int32, device="cuda"), out=out)
+    want = np.full((6, 8), -5, dtype=np.int32)
+    for r, s in enumerate([3, -1, 49, 50, 0, 7]):
+        if 0 <= s < 50:
+            want[r] = src[s, 4:12]
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("layers,row_elems", [(1, 8), (3, 1024), (5, 8 * 128)])
+def test_commit_kv_matches_oracle(gpu, layers, row_elems):
+    import paper_2407_16207_amd as gsd
+    rng = np.random.default_rng(layers * 1000 + row_elems)
+    B, N = 6, 40
+    prefix_lens = np.array([5, 0, 33, 7, 64, 1], dtype=np.int32)
+    rows = int((prefix_lens + N).sum())
+    kv_offsets = np.concatenate([[0], np.cumsum(prefix_lens + N)[:-1]]).astype(np.int64)
+    k = rng.integers(0, 1 << 16, size=(layers, rows, 1, row_elems)).astype(np.uint16)
+    v = rng.integers(0, 1 << 16, size=(layers, rows, 1, row_elems)).astype(np.uint16)
+    accept_len = np.array([12, 0, 40, 1, 23, 9], dtype=np.int32)
+    accept_path = np.full((B, N), -1, dtype=np.int32)
+    for b in range(B):
+        if b == 2:
+            accept_path[b] = np.arange(N)                          # fully accepted chain: nothing moves
+        else:
+            accept_path[b, :accept_len[b]] = np.sort(rng.choice(N, size=accept_len[b], replace=False))
+    accept_path[5, :9] = np.arange(1, 10)                          # every destination is the next row's source
+    nk, nv, nl = gsd_next.commit_kv(k, v, kv_offsets, prefix_lens, accept_len, accept_path)
+    dk = torch.from_numpy(k.view(np.int16)).cuda()
+    dv = torch.from_numpy(v.view(np.int16)).cuda()
+    got_len = gsd.gsd_commit_kv(dk, dv, gpu.to_dev(kv_offsets), gpu.to_dev(prefix_lens), gpu.to_dev(accept_len),
+                                gpu.to_dev(accept_path))
+    torch.cuda.synchronize()
+    assert np.array_equal(got_len.cpu().numpy(), nl)
+    assert np.array_equal(dk.cpu().numpy().view(np.uint16), nk)
+    assert np.array_equal(dv.cpu().numpy().view(np.uint16), nv)
+
+
+def test_tree_verification_end_to_end(gpu):
+    """The paper's exact variant: un-merge, carry per-node data to the replicas, then the same mask / attention /
+    acceptance calls on the tree.  Checked against the oracle applied to the oracle's tree; the accepted path,
+    mapped back through `origin`, is the one found on the graph directly."""
+    import paper_2407_16207_amd as gsd
+    from oracle import gsd_ref
+    rng = np.random.default_rng(2024)
+    B, N, Hq, Hkv, D, P, V = 3, 96, 8, 2, 128, 200, 211
+    cfg = VerifyConfig("tree-e2e", B, Hq, Hkv, D, P, P, 1, N, 2, V, 0.8, "bf16")
+    w = make_workload(cfg, seed=99)
+    dags = [merged_tree_dag(rng, N, 3, 8) for _ in range(B)]
+    node_offsets, poff, pidx = pack(dags)
+    tokens = rng.integers(0, 5, B * N).astype(np.int32)
+    pred = rng.integers(0, 5, B * N).astype(np.int32)
+    root_pred = rng.integers(0, 5, B).astype(np.int32)
+    cap = 512
+    d_no, d_po, d_pi = gpu.to_dev(node_offsets), gpu.to_dev(poff), gpu.to_dev(pidx)
+    t_no, t_par, t_po, t_org, cnt = gsd.gsd_unmerge_to_tree(d_no, d_po, d_pi, N, cap)
+    ro, rtp, rto, rcnt = gsd_next.unmerge_to_tree(node_offsets, poff, pidx, cap)
+    o = t_no.cpu().numpy()
+    Tt = int(o[-1])
+    assert np.array_equal(o, ro) and Tt > B * N and (rcnt <= cap).all()
+    sizes = np.diff(o)
+    n_max = int(sizes.max())
+    # packed source rows of every replica (setup arithmetic on indices, not part of the method)
+    seq_of = np.repeat(np.arange(B), sizes)
+    src_node = torch.from_numpy((node_offsets[seq_of] + rto).astype(np.int32)).cuda()
+    q_t = gsd.gsd_gather_rows(gpu.to_dev(w.q), src_node)
+    tok_t = gsd.gsd_gather_rows(gpu.to_dev(tokens), src_node)
+    pred_t = gsd.gsd_gather_rows(gpu.to_dev(pred), src_node)
+    # K/V of the tree pass: each sequence's prefix rows, then its replicas' rows
+    kv_rows = w.prefix_lens.astype(np.int64) + sizes
+    t_kv_offsets = np.concatenate([[0], np.cumsum(kv_rows)[:-1]]).astype(np.int64)
+    src_kv = np.concatenate([np.concatenate([w.kv_offsets[b] + np.arange(P),
+                                             w.kv_offsets[b] + P + rto[o[b]:o[b + 1]]]) for b in range(B)])
+    src_kv_t = torch.from_numpy(src_kv.astype(np.int32)).cuda()
+    k_t = gsd.gsd_gather_rows(gpu.to_dev(w.k), src_kv_t)
+    v_t = gsd.gsd_gather_rows(gpu.to_dev(w.v), src_kv_t)
+    t_par, t_po = t_par[:Tt].contiguous(), t_po[:Tt + 1].contiguous()
+    mask = gsd.gsd_build_mask(t_no, t_po, t_par, n_max)
+    out = gsd.gsd_dag_attention(q_t, k_t, v_t, gpu.to_dev(t_kv_offsets), gpu.to_dev(w.prefix_lens), t_no, mask,
+                                n_max, P, w.softmax_scale)
+    ln, path, bonus, _ = gsd.gsd_accept_longest_path(t_no, t_po, t_par, tok_t, gpu.to_dev(root_pred), n_max,
+                                                     pred=pred_t)
+    torch.cuda.synchronize()
+    # oracle on the oracle's tree
+    rmask, _ = gsd_ref.build_mask(ro, np.arange(Tt + 1), rtp)
+    assert np.array_equal(gpu.mask_to_numpy(mask), rmask)
+    ref_out = gsd_ref.dag_attention(w.q[src_node.cpu().numpy()], w.k[src_kv], w.v[src_kv], t_kv_offsets,
+                                    w.prefix_lens, ro, rmask, w.softmax_scale)
+    assert np.abs(gpu.out_to_f64(out) - ref_out).max() <= 2e-2
+    rl, rpath, rbonus = gsd_ref.accept_longest_path(ro, np.arange(Tt + 1), rtp, tokens[src_node.cpu().numpy()],
+                                                    pred[src_node.cpu().numpy()], root_pred, max_nodes=n_max)
+    assert np.array_equal(ln.cpu().numpy(), rl) and np.array_equal(path.cpu().numpy(), rpath)
+    assert np.array_equal(bonus.cpu().numpy(), rbonus)
+    # mapped back to graph ids it is the graph's own longest accepted path
+    dl, dpath, dbonus = gsd_ref.accept_longest_path(node_offsets, poff, pidx, tokens, pred, root_pred)
+    for b in range(B):
+        tree_ids = rpath[b, :rl[b]]
+        assert rto[o[b] + tree_ids].tolist() == dpath[b, :dl[b]].tolist()
+    assert np.array_equal(dbonus, rbonus) and (rl > 0).any()
