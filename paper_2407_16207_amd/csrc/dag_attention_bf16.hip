@@ -102,10 +102,17 @@ __device__ __forceinline__ void dma16(const void *gbase, uint32_t voff, uint32_t
 template <int N> __device__ __forceinline__ void dma_wait() {   // at most N vector-memory operations in flight
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
+// A wave-uniform 64-bit value, forced into scalar registers (the copies above take their base address from there;
+// a uniform value loaded through the vector memory path would otherwise stay in vector registers).
+__device__ __forceinline__ int64_t uniform64(int64_t x) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(x)));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(uint32_t(uint64_t(x) >> 32));
+    return int64_t((uint64_t(hi) << 32) | lo);
+}
+// Work-group barrier as bare assembly: the compiler's own barrier is preceded by a wait for every outstanding LDS
+// read, which would undo the reads issued ahead of it on purpose (their results are awaited where they are used).
 __device__ __forceinline__ void wg_barrier() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    asm volatile("s_barrier" ::: "memory");
 }
 
 // NW wavefronts per work-group, 32 query rows each: 8 (256 rows, one work-group per CU) halves the K/V traffic into
@@ -244,8 +251,9 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // +l/CHUNKS, 16-byte slot l%CHUNKS, and therefore fetches the chunk that the swizzle assigns to that slot.
     static_assert(RPI % 4 == 0 && (RPI == 4 || RPI == 8), "row bookkeeping below assumes 4 or 8 rows per copy");
     static_assert(IPW >= 1 && IPW * (kThreads / 64) * 1024 == L::kTileBytes, "the waves' copies must tile the buffer");
-    const __bf16 *k_seq = p.k + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
-    const __bf16 *v_seq = p.v + p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs;
+    const int64_t kv_elem_off = uniform64(p.kv_offsets[b] * p.kv_ts + int64_t(kvh) * p.kv_hs);
+    const __bf16 *k_seq = p.k + kv_elem_off;
+    const __bf16 *v_seq = p.v + kv_elem_off;
     const uint32_t row_stride_bytes = uint32_t(p.kv_ts) * 2u;
     const int32_t last_row = P + n - 1;            // last K/V row of the sequence: loads are clamped to it
     // Copy j = 0 decides everything: later copies only add compile-time constants (rows) or flip one chunk bit.
@@ -352,12 +360,21 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // end of the running-max update for the tile whose in-lane max is mx
     // mx: in-lane max of the tile's shifted scores `sc`.  Moves the offset where it has to (rarely), fixing up this
     // tile's scores, the running sum and m_vec; the accumulators are rescaled by the caller (need_rescale, alpha).
-    auto finish_max = [&](float mx, floatx16 (&sc)[2]) __attribute__((always_inline)) {
+    // Two parts, so that the caller can put a matrix instruction or two between them: the decision (a chain of
+    // dependent vector, scalar and compare instructions; plain bit operations on the lane masks, no branches), and the
+    // rarely taken fix-up behind a wave-uniform branch.
+    bool grow = false;
+    float mx_tile = 0.f;
+    auto decide_max = [&](float mx) __attribute__((always_inline)) {
         mx = max_across_halves(mx);
         const bool seen = mx > -__builtin_inff();
-        const bool grow = seen && (mx > kLazyMax || !m_set);
-        m_set = m_set || seen;
+        grow = seen & ((mx > kLazyMax) | !m_set);
+        m_set = m_set | seen;
         need_rescale = __any(grow);
+        mx_tile = mx;
+    };
+    auto apply_max = [&](floatx16 (&sc)[2]) __attribute__((always_inline)) {
+        const float mx = mx_tile;
         alpha = 1.f;
         if (need_rescale) {
             const float delta = grow ? mx : 0.f;
@@ -375,19 +392,26 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
 
     // ---- the software pipeline ---------------------------------------------------------------------------------
     // Live tiles are taken in order i = 0, 1, ...; at the top of step i
-    //   registers   shifted (masked) scores of tile i, with m_run / alpha already updated for it
-    //   LDS         K(i+1) in K buffer (i+1)&1, complete and published
-    //   in flight   copies issued in the order V(i), K(i+2) -> K buffer i&1 (V(i+1) is issued during phase A)
+    //   registers   shifted (masked) scores of tile i, with m_run / alpha already updated for it, and the first four
+    //               K fragments of tile i+1
+    //   LDS         K(i+1) in K buffer (i+1)&1 and V(i) in V buffer i&1, complete and published
+    //   in flight   the copy of K(i+2) -> K buffer i&1 (V(i+1) is issued during phase A)
     // Step i:  [rescale acc_o if the max moved]
     //          phase A: scores of tile i+1 on the matrix pipe while the vector ALU turns the scores of tile i
-    //                   into bf16 probabilities
-    //          wait for V(i)'s copy, barrier (now the K buffer just read may be refilled with K(i+3), in phase B)
+    //                   into bf16 probabilities; its last slices read the first V fragments of tile i
+    //          wait for K(i+2)'s copy, barrier (now the K buffer just read may be refilled with K(i+3), in phase B)
     //          phase B: O^T += V^T P^T on the matrix pipe while the vector ALU reduces the running max of the
-    //                   new scores (masked first if tile i+1 needs it)
-    //          wait for K(i+2)'s copy, barrier (now the V buffer just read may be refilled, in the next phase A)
-    // Each wait leaves the two younger copies in flight (2*IPW operations); near the end of the range, where
-    // those copies do not exist, it waits for everything.
+    //                   new scores (masked first if tile i+1 needs it); its last slices read the first K fragments
+    //                   of tile i+2
+    //          wait for V(i+1)'s copy, barrier (now the V buffer just read may be refilled, in the next phase A)
+    // Each wait leaves the youngest copy in flight (IPW operations); near the end of the range, where that copy does
+    // not exist, it waits for everything.  A tile is thus published one barrier before the phase that consumes it,
+    // which is what lets that phase's first fragments be read ahead of the barrier in front of it.
     u32x4 pf[4];               // bf16 probabilities of the tile, two per register, in accumulator-register order
+    // The first four fragments of a phase are read from LDS during the last slices of the phase before it, ahead
+    // of the barrier between them (the tile they come from was published one barrier earlier), so that the matrix
+    // pipe does not idle for an LDS round trip after every barrier.
+    bf16x8 kpre[4], vpre[4];
 
     auto rescale = [&]() __attribute__((always_inline)) {
         if (need_rescale) {
@@ -409,6 +433,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         const bf16x2 pr = __builtin_convertvector(x, bf16x2);
         pf[e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, pr);
         sum += x[0] + x[1];
+        asm volatile("" : "+v"(sum));      // keeps the two additions in this slice (they would be collected behind the last one)
     };
 
     // The exponentials are the vector ALU's heaviest load, so they are split between the two phases: phase B of
@@ -418,7 +443,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next, and spread
     // the copy of the next tile's V (tile `v_tile` into V buffer `v_buf`) over the slices: issued back to back after
     // a barrier, the copies of all the waves queue up in the texture path.
-    auto phase_a = [&](auto has_next_tag, auto full_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf) __attribute__((always_inline)) {
+    auto phase_a = [&](auto has_next_tag, auto full_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf, int v_cur) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;     // the tile being copied is a full prefix tile
         constexpr int EVERY = NQK / 8;              // one pair of scores every EVERY slices
@@ -426,7 +451,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         bf16x8 kf[NQK];
         if (HAS_NEXT) {
 #pragma unroll
-            for (int x = 0; x < 4; ++x) kf[x] = k_frag(kbuf, x);
+            for (int x = 0; x < 4; ++x) kf[x] = kpre[x];
+        } else {
+#pragma unroll
+            for (int x = 0; x < 4; ++x) vpre[x] = v_frag(v_cur, x);
         }
         GSD_SLICE_END();
 #pragma unroll
@@ -434,6 +462,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             if (HAS_NEXT) {
                 s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], idx < 2 ? m_vec : s_next[idx & 1], 0, 0, 0);
                 if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
+                else vpre[idx + 4 - NQK] = v_frag(v_cur, idx + 4 - NQK);   // phase B's first reads, ahead of the barrier
                 if (idx % (NQK / IPW) == 1) {
                     if (FULL) dma_v_one_full(v_tile, v_buf, idx / (NQK / IPW));
                     else dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
@@ -453,7 +482,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // is not a full prefix tile, reduces its max (first quarter of the slices), updates the running max and the
     // running sum, and converts scores 0..15 (second half of the slices; pf[0] and pf[1] have been consumed by then).
     // COPY_K spreads the copy of tile `k_tile` into K buffer `k_buf` over the slices.
-    auto phase_b = [&](auto has_next_tag, auto copy_k_tag, auto full_tag, int vbuf, floatx16 (&s_next)[2], int next_tile, int k_tile, int k_buf) __attribute__((always_inline)) {
+    auto phase_b = [&](auto has_next_tag, auto copy_k_tag, auto full_tag, int vbuf, floatx16 (&s_next)[2], int next_tile, int k_tile, int k_buf, bool k_ahead, int k_next_buf) __attribute__((always_inline)) {
         constexpr bool COPY_K = decltype(copy_k_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
@@ -463,8 +492,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         constexpr int CONV_PER_SLICE = 8 / (NPV / 2);   // pairs converted per slice
         bf16x8 vf[NPV];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) vf[x] = v_frag(vbuf, x);
-        if (HAS_NEXT && next_tile >= full_end) apply_mask(s_next, next_tile);
+        for (int x = 0; x < 4; ++x) vf[x] = vpre[x];
+        if (HAS_NEXT && !FULL && next_tile >= full_end) apply_mask(s_next, next_tile);   // FULL: the next tile is a full prefix tile too
         float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
         float sum = 0.f;
         GSD_SLICE_END();
@@ -473,6 +502,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             const int ks2 = idx / MBD, mbd = idx % MBD;
             acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, pf[ks2]), acc_o[mbd], 0, 0, 0);
             if (idx + 4 < NPV) vf[idx + 4] = v_frag(vbuf, idx + 4);
+            else if (HAS_NEXT && k_ahead) kpre[idx + 4 - NPV] = k_frag(k_next_buf, idx + 4 - NPV);   // next phase A's first reads
             if (COPY_K && idx % (NPV / IPW) == 1) {
                 if (FULL) dma_k_one_full(k_tile, k_buf, idx / (NPV / IPW));
                 else dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
@@ -486,7 +516,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
                         else mx0 = max3(mx0, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
                     }
                 }
-                if (idx == MAX_SLICES) finish_max(fmaxf(mx0, mx1), s_next);
+                if (idx == MAX_SLICES) decide_max(fmaxf(mx0, mx1));
+                if (idx == CONV_FIRST - 1) apply_max(s_next);
                 if (idx >= CONV_FIRST) {
 #pragma unroll
                     for (int x = 0; x < CONV_PER_SLICE; ++x)
@@ -528,7 +559,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sa[mb][j]);
-            finish_max(mx, sa);
+            decide_max(mx);
+            apply_max(sa);
             float sum = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; e += 2) convert_pair(sa, e, sum);
@@ -542,6 +574,10 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             dma_wait<0>();
         }
         wg_barrier();
+        if (c1 < t_end) {
+#pragma unroll
+            for (int x = 0; x < 4; ++x) kpre[x] = k_frag(1, x);
+        }
 
         int i = 0;
         // one step with the current scores in `cur`, leaving the next tile's scores in `nxt`.  STEADY: tiles
@@ -551,12 +587,12 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             constexpr bool STEADY = decltype(steady_tag)::value;
             constexpr bool FAST = decltype(fast_tag)::value;
             rescale();
-            phase_a(True{}, fast_tag, (i + 1) & 1, cur, nxt, c1, (i + 1) & 1);    // also starts the copy of V(i+1)
-            if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // V(i) has landed
+            phase_a(True{}, fast_tag, (i + 1) & 1, cur, nxt, c1, (i + 1) & 1, i & 1);   // also starts the copy of V(i+1)
+            if (STEADY) dma_wait<IPW>(); else dma_wait<0>();             // K(i+2) has landed (V(i) did a barrier ago)
             wg_barrier();
             if (!STEADY && c3 < t_end) dma_k(c3, (i + 1) & 1);
-            phase_b(True{}, steady_tag, fast_tag, i & 1, nxt, c1, c3, (i + 1) & 1);   // steady: also copies K(i+3)
-            if (STEADY) dma_wait<2 * IPW>(); else dma_wait<0>();         // K(i+2) has landed
+            phase_b(True{}, steady_tag, fast_tag, i & 1, nxt, c1, c3, (i + 1) & 1, STEADY || c2 < t_end, i & 1);   // steady: also copies K(i+3)
+            if (STEADY) dma_wait<IPW>(); else dma_wait<0>();             // V(i+1) has landed
             wg_barrier();
             c0 = c1; c1 = c2; c2 = c3; c3 = FAST ? c3 + 1 : next_live(c3);
             ++i;
@@ -578,8 +614,8 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         }
         // last tile: nothing left to prefetch or to score
         rescale();
-        phase_a(False{}, False{}, 0, sa, sb, 0, 0);
-        phase_b(False{}, False{}, False{}, i & 1, sb, 0, 0, 0);
+        phase_a(False{}, False{}, 0, sa, sb, 0, 0, i & 1);
+        phase_b(False{}, False{}, False{}, i & 1, sb, 0, 0, 0, false, 0);
     }
 
     // ---- epilogue ------------------------------------------------------------------------------------------
