@@ -107,7 +107,8 @@ typedef struct gsd_attn_desc {
     int32_t words_per_row; /* uint64 words per mask row, >= ceil(max_nodes/64) */
     int32_t num_splits;    /* KV splits: 0 = let the library choose, >= 1 = forced */
     float softmax_scale;   /* e.g. 1/sqrt(D) */
-    int32_t wg_waves;      /* tuning: wavefronts per work-group of the bf16 kernel, 0 = let the library choose, else 4 or 8 */
+    int32_t wg_waves;      /* tuning: work-group shape of the bf16 kernel: 0 = let the library choose; 4 or 8 = that many
+                              wavefronts of 32 query rows each; 64 = 4 wavefronts of 64 query rows each */
     const void *q;         /* [T][Hq][D] via strides */
     void *o;               /* same shape and dtype as q */
     float *lse;            /* [T][Hq] contiguous, or NULL */

@@ -115,13 +115,37 @@ __device__ __forceinline__ void wg_barrier() {
     asm volatile("s_barrier" ::: "memory");
 }
 
-// NW wavefronts per work-group, 32 query rows each: 8 (256 rows, one work-group per CU) halves the K/V traffic into
-// LDS and the number of copies each wave issues per tile; 4 (128 rows, two work-groups per CU) wastes less when a
-// (sequence, KV head) has few rows.
-template <int D, int NW>
-__global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(const AttnParams p) {
+// Matrix instructions written out for the one-wave-per-SIMD variant.  With 512 registers per lane the compiler
+// selects the accumulator-register form for every matrix instruction it emits itself, and then moves every score
+// into an ordinary register before the softmax can touch it.  Written out, the score accumulators stay in ordinary
+// registers ("v") and only the output accumulators and the query fragments, which the vector ALU never reads in
+// the loop, live in accumulator registers ("a").  The compiler does not know these are matrix instructions, so
+// the two places where the vector ALU reads their results soon after them wait by hand (mfma_settle).
+__device__ __forceinline__ void mfma_v_acc(floatx16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma_v_init(floatx16 &acc, const bf16x8 &a, const bf16x8 &b, const floatx16 &c) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=v"(acc) : "v"(a), "a"(b), "v"(c));   // C and D share a file
+}
+__device__ __forceinline__ void mfma_a_acc(floatx16 &acc, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// at least 16 issue cycles: longer than the 12 the vector ALU must keep away from an 8-pass matrix result
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 7\n\ts_nop 7" ::: "memory"); }
+
+// NW wavefronts per work-group, each owning RBW blocks of 32 query rows.
+//   <4 waves, 2 blocks>  256 rows, one work-group per CU, one wave per SIMD with the whole register file: every K/V
+//                        fragment read from LDS feeds two matrix instructions, so the instructions a wave has to
+//                        issue per matrix instruction (LDS reads, waits, copies, loop control) halve.  On this chip a
+//                        wave issues about one instruction every four cycles and two waves of a SIMD do not overlap
+//                        their matrix and vector work, so that count is what bounds the kernel.
+//   <8 waves, 1 block>   256 rows, two waves per SIMD.
+//   <4 waves, 1 block>   128 rows, two work-groups per CU: wastes less when a (sequence, KV head) has few rows.
+template <int D, int NW, int RBW>
+__global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_bf16_kernel(const AttnParams p) {
     constexpr int kThreads = NW * 64;
-    constexpr int kRowsPerWG = NW * 32;
+    constexpr int kRowsPerWG = NW * 32 * RBW;
+    constexpr bool ASM_MFMA = RBW == 2;
     constexpr int KS = D / 16;          // k-steps of the first contraction
     constexpr int MBD = D / 32;         // 32-channel blocks of the output
     constexpr int NQK = 2 * KS;         // matrix instructions of S^T = K Q^T per tile
@@ -164,14 +188,16 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     const int32_t row0 = qt * kRowsPerWG;
     if (row0 >= rows_total) return;                // uniform for the work-group
 
-    const int32_t my_row = row0 + wave * 32 + col;
-    const bool row_valid = my_row < rows_total;
-    const int32_t row_c = row_valid ? my_row : rows_total - 1;
-    const int32_t node = row_c / G;
-    const int32_t g = row_c - node * G;
-    const int32_t head = kvh * G + g;
-    const int64_t t = int64_t(node_base) + node;
-    const uint64_t *mrow = p.mask + t * p.words_per_row;
+    // row block rb of this wave: rows row0 + (wave*RBW + rb)*32 .. +31, this lane's row is +col
+    auto row_of = [&](int rb) __attribute__((always_inline)) -> int32_t { return row0 + (wave * RBW + rb) * 32 + col; };
+    auto row_is_valid = [&](int rb) __attribute__((always_inline)) -> bool { return row_of(rb) < rows_total; };
+    auto node_of = [&](int rb) __attribute__((always_inline)) -> int32_t {   // rows past the end stand in for the last row
+        return min(row_of(rb), rows_total - 1) / G;
+    };
+    auto head_of = [&](int rb) __attribute__((always_inline)) -> int32_t {
+        const int32_t r = min(row_of(rb), rows_total - 1);
+        return kvh * G + (r - (r / G) * G);
+    };
 
     // ---- KV tile range of this split -----------------------------------------------------------------------
     const int ntp = (P + kKeysPerTile - 1) / kKeysPerTile;
@@ -187,18 +213,28 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // behind the tile copies in the in-order memory counter and stall the wave for a full memory round trip.
     constexpr int kMaxWords = GSD_MAX_NODES_PER_SEQ / 64;
     __shared__ uint64_t mask_lds[kRowsPerWG * kMaxWords];
-    uint64_t *my_mask = mask_lds + (wave * 32 + col) * kMaxWords;      // both halves of the wave write the same words
+    // words of row block rb: my_mask + rb*32*kMaxWords (both halves of the wave write the same words)
+    uint64_t *my_mask = mask_lds + (wave * RBW * 32 + col) * kMaxWords;
     uint64_t live = 0;
     {
-        uint64_t words[kMaxWords];
+        uint64_t seen_any[kMaxWords];
 #pragma unroll
-        for (int j = 0; j < kMaxWords; ++j) words[j] = (row_valid && j < ntd) ? mrow[j] : 0;
+        for (int j = 0; j < kMaxWords; ++j) seen_any[j] = 0;
 #pragma unroll
-        for (int j = 0; j < kMaxWords; ++j) my_mask[j] = words[j];
+        for (int rb = 0; rb < RBW; ++rb) {
+            const uint64_t *mrow = p.mask + (int64_t(node_base) + node_of(rb)) * p.words_per_row;
+            const bool ok = row_is_valid(rb);
+#pragma unroll
+            for (int j = 0; j < kMaxWords; ++j) {
+                const uint64_t w = (ok && j < ntd) ? mrow[j] : 0;
+                my_mask[rb * 32 * kMaxWords + j] = w;
+                seen_any[j] |= w;
+            }
+        }
         for (int j = 0; j < ntd; ++j) {
             uint64_t w = 0;
 #pragma unroll
-            for (int x = 0; x < kMaxWords; ++x) w = (x == j) ? words[x] : w;
+            for (int x = 0; x < kMaxWords; ++x) w = (x == j) ? seen_any[x] : w;
             if (__syncthreads_or(w != 0)) live |= uint64_t(1) << (j & 63);
         }
     }
@@ -214,37 +250,53 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     };
 
     // ---- Q fragments: B operand of S^T = K Q^T; lane holds Q[row][ks*16 + 8*half .. +7] ------------------------
-    bf16x8 qf[KS];
-    {
-        const __bf16 *qp = p.q + t * p.q_ts + int64_t(head) * p.q_hs + 8 * half;
+    bf16x8 qf[RBW][KS];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
+    for (int rb = 0; rb < RBW; ++rb) {
+        const __bf16 *qp = p.q + (int64_t(node_base) + node_of(rb)) * p.q_ts + int64_t(head_of(rb)) * p.q_hs + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[rb][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
         // Fold softmax_scale*log2(e) into Q once (rounded back to bf16), so that the matrix pipe delivers the
         // exponent of 2 directly and the vector ALU spends no multiply per score.
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-            for (int z = 0; z < 8; ++z) qf[ks][z] = (__bf16)((float)qf[ks][z] * p.scale_log2e);
+            for (int z = 0; z < 8; ++z) qf[rb][ks][z] = (__bf16)((float)qf[rb][ks][z] * p.scale_log2e);
+        // resident in the accumulator file from here on (otherwise each use copies its fragment over again)
+        if (ASM_MFMA) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[rb][ks]));
+        }
     }
 
-    floatx16 acc_o[MBD];
+    floatx16 acc_o[RBW][MBD];
 #pragma unroll
-    for (int i = 0; i < MBD; ++i)
+    for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc_o[i][j] = 0.f;
+        for (int i = 0; i < MBD; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc_o[rb][i][j] = 0.f;
     // Scores leave the matrix pipe already in the exponent's domain and already shifted: the first matrix
     // instruction of every score block accumulates onto m_vec, sixteen copies of -m_run.  m_run is the row's
     // offset, not its exact running max: it is raised only when a score exceeds it by more than kLazyMax (softmax
     // does not care which offset is used, and 2^8 is nowhere near the range of fp32 or bf16), so in the steady
     // state no rescaling and no per-score subtraction happens at all.
-    float m_run = 0.f;         // offset (log2 domain) applied to the tile whose scores are held
-    bool m_set = false;        // the offset has been taken from real scores (the first visible key sets it)
-    floatx16 m_vec;
+    float m_run[RBW];          // offset (log2 domain) applied to the tile whose scores are held
+    bool m_set[RBW];           // the offset has been taken from real scores (the first visible key sets it)
+    floatx16 m_vec[RBW];
+    float l_run[RBW];          // this lane's share of the running sum (the other half lives in lane^32)
+    float alpha[RBW];          // pending rescale of acc_o / l_run for the tile whose scores are held
+    bool need_rescale[RBW];    // wave-uniform: some lane's max moved
 #pragma unroll
-    for (int j = 0; j < 16; ++j) m_vec[j] = 0.f;
-    float l_run = 0.f;         // this lane's share of the running sum (the other half lives in lane^32)
-    float alpha = 1.f;         // pending rescale of acc_o / l_run for the tile whose scores are held
-    bool need_rescale = false; // wave-uniform: some lane's max moved
+    for (int rb = 0; rb < RBW; ++rb) {
+        m_run[rb] = 0.f;
+        m_set[rb] = false;
+        l_run[rb] = 0.f;
+        alpha[rb] = 1.f;
+        need_rescale[rb] = false;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) m_vec[rb][j] = 0.f;
+    }
 
     // ---- global -> LDS copies of K/V tiles ----------------------------------------------------------------------
     // Copy j of this wave fills LDS rows (wave*IPW + j)*RPI .. +RPI-1 of the tile buffer; lane l lands in row
@@ -276,22 +328,26 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         dma16(v_seq, __umul24(r, row_stride_bytes) + v_src_chunk,
               lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
     };
-    // The same copies for a tile whose 64 rows all exist (a full prefix tile): no clamp, the lane's offset is a
-    // constant and the tile's and the copy's share of the address is scalar arithmetic on the base pointer.
-    uint32_t k_lane_off[IPW];
+    // The same copies over a run of consecutive full prefix tiles (all 64 rows exist, no clamp): every lane keeps
+    // the byte offset of its next chunk and adds one tile's worth after each copy, which is all the address
+    // arithmetic left (the general form costs a chain of about ten dependent scalar instructions per copy).
+    uint32_t k_run[IPW], v_run[IPW];
+    const uint32_t tile_stride_bytes = uint32_t(kKeysPerTile) * row_stride_bytes;
+    auto start_full_run = [&](int k_tile, int v_tile) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < IPW; ++j)
-        k_lane_off[j] = uint32_t(k_lds_row(lane / CHUNKS)) * row_stride_bytes + (k_src_chunk0 ^ uint32_t(k_swz(j * RPI) * 16));
-    const uint32_t v_lane_off = uint32_t(lane / CHUNKS) * row_stride_bytes + v_src_chunk;
-    auto dma_k_one_full = [&](int ti, int buf, int j) __attribute__((always_inline)) {
-        const int32_t row = ti * kKeysPerTile + k_lds_row(wave * IPW * RPI + j * RPI);
-        dma16(reinterpret_cast<const char *>(k_seq) + int64_t(row) * row_stride_bytes, k_lane_off[j],
-              lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
+        for (int j = 0; j < IPW; ++j) {
+            k_run[j] = uint32_t(k_tile * kKeysPerTile + k_lds_row(m0) + k_lds_row(j * RPI)) * row_stride_bytes +
+                       (k_src_chunk0 ^ uint32_t(k_swz(j * RPI) * 16));
+            v_run[j] = uint32_t(v_tile * kKeysPerTile + m0 + j * RPI) * row_stride_bytes + v_src_chunk;
+        }
     };
-    auto dma_v_one_full = [&](int ti, int buf, int j) __attribute__((always_inline)) {
-        const int32_t row = ti * kKeysPerTile + wave * IPW * RPI + j * RPI;
-        dma16(reinterpret_cast<const char *>(v_seq) + int64_t(row) * row_stride_bytes, v_lane_off,
-              lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
+    auto dma_k_one_full = [&](int buf, int j) __attribute__((always_inline)) {
+        dma16(k_seq, k_run[j], lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
+        k_run[j] += tile_stride_bytes;
+    };
+    auto dma_v_one_full = [&](int buf, int j) __attribute__((always_inline)) {
+        dma16(v_seq, v_run[j], lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
+        v_run[j] += tile_stride_bytes;
     };
     auto dma_k = [&](int ti, int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -342,11 +398,11 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     // mask of tile `ti` applied to the raw scores: register i of block mb is key mb*32 + 16*(i/8) + 8*half + i%8
-    auto apply_mask = [&](floatx16 (&sc)[2], int ti) __attribute__((always_inline)) {
+    auto apply_mask = [&](floatx16 (&sc)[2], int ti, int rb) __attribute__((always_inline)) {
         const bool is_draft = ti >= ntp;
         const int32_t valid = is_draft ? min(kKeysPerTile, n - (ti - ntp) * kKeysPerTile)
                                        : min(kKeysPerTile, P - ti * kKeysPerTile);
-        uint64_t vis = is_draft ? my_mask[ti - ntp] : ~uint64_t(0);
+        uint64_t vis = is_draft ? my_mask[rb * 32 * kMaxWords + ti - ntp] : ~uint64_t(0);
         if (valid < kKeysPerTile) vis &= (uint64_t(1) << valid) - 1;
         vis >>= 8 * half;
 #pragma unroll
@@ -363,26 +419,25 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // Two parts, so that the caller can put a matrix instruction or two between them: the decision (a chain of
     // dependent vector, scalar and compare instructions; plain bit operations on the lane masks, no branches), and the
     // rarely taken fix-up behind a wave-uniform branch.
-    bool grow = false;
-    float mx_tile = 0.f;
-    auto decide_max = [&](float mx) __attribute__((always_inline)) {
+    bool grow[RBW];
+    float mx_tile[RBW];
+    auto decide_max = [&](float mx, int rb) __attribute__((always_inline)) {
         mx = max_across_halves(mx);
         const bool seen = mx > -__builtin_inff();
-        grow = seen & ((mx > kLazyMax) | !m_set);
-        m_set = m_set | seen;
-        need_rescale = __any(grow);
-        mx_tile = mx;
+        grow[rb] = seen & ((mx > kLazyMax) | !m_set[rb]);
+        m_set[rb] = m_set[rb] | seen;
+        need_rescale[rb] = __any(grow[rb]);
+        mx_tile[rb] = mx;
     };
-    auto apply_max = [&](floatx16 (&sc)[2]) __attribute__((always_inline)) {
-        const float mx = mx_tile;
-        alpha = 1.f;
-        if (need_rescale) {
-            const float delta = grow ? mx : 0.f;
-            m_run += delta;
-            alpha = __builtin_amdgcn_exp2f(-delta);
-            l_run *= alpha;
+    auto apply_max = [&](floatx16 (&sc)[2], int rb) __attribute__((always_inline)) {
+        alpha[rb] = 1.f;
+        if (need_rescale[rb]) {
+            const float delta = grow[rb] ? mx_tile[rb] : 0.f;
+            m_run[rb] += delta;
+            alpha[rb] = __builtin_amdgcn_exp2f(-delta);
+            l_run[rb] *= alpha[rb];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) m_vec[j] = -m_run;
+            for (int j = 0; j < 16; ++j) m_vec[rb][j] = -m_run[rb];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -407,47 +462,66 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     // Each wait leaves the youngest copy in flight (IPW operations); near the end of the range, where that copy does
     // not exist, it waits for everything.  A tile is thus published one barrier before the phase that consumes it,
     // which is what lets that phase's first fragments be read ahead of the barrier in front of it.
-    u32x4 pf[4];               // bf16 probabilities of the tile, two per register, in accumulator-register order
+    u32x4 pf[RBW][4];          // bf16 probabilities of the tile, two per register, in accumulator-register order
     // The first four fragments of a phase are read from LDS during the last slices of the phase before it, ahead
     // of the barrier between them (the tile they come from was published one barrier earlier), so that the matrix
     // pipe does not idle for an LDS round trip after every barrier.
     bf16x8 kpre[4], vpre[4];
 
-    auto rescale = [&]() __attribute__((always_inline)) {
-        if (need_rescale) {
-#pragma unroll
-            for (int x = 0; x < MBD; ++x)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc_o[x][j] *= alpha;
+    // matrix instruction idx (0..NQK-1) of a tile's scores for row block rb: the first of each chain starts from m_vec
+    auto score_mfma = [&](floatx16 &acc, const bf16x8 &kfrag, int rb, int idx) __attribute__((always_inline)) {
+        if (ASM_MFMA) {
+            if (idx < 2) mfma_v_init(acc, kfrag, qf[rb][idx >> 1], m_vec[rb]);
+            else mfma_v_acc(acc, kfrag, qf[rb][idx >> 1]);
+        } else {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[rb][idx >> 1], idx < 2 ? m_vec[rb] : acc, 0, 0, 0);
         }
+    };
+    auto rescale = [&]() __attribute__((always_inline)) {
+        if (ASM_MFMA && (need_rescale[0] || need_rescale[RBW - 1])) mfma_settle();
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb)
+            if (need_rescale[rb]) {
+#pragma unroll
+                for (int x = 0; x < MBD; ++x) {
+                    // take the value from the accumulator file and hand the product back to it inside the branch, or
+                    // the copies out of and into that file are hoisted in front of the branch and run on every step
+                    if (ASM_MFMA) asm volatile("" : "+a"(acc_o[rb][x]));
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) acc_o[rb][x][j] *= alpha[rb];
+                    if (ASM_MFMA) asm volatile("" : "+a"(acc_o[rb][x]));
+                }
+            }
     };
     // scores e and e+1 of `sc` (already shifted exponents of 2) -> bf16 probabilities, stored in accumulator-register
     // order, and added to the lane's running sum.  Plain v_add_f32 on purpose: measured on this chip, ordinary vector
     // instructions (add, fma, max3, cvt_pk_bf16) issue in the shadow of a running matrix instruction for free and
     // v_exp_f32 for three quarters, but v_dot2c_f32_bf16 (one instruction per pair) runs on the matrix pipe itself,
     // takes ~2.5x as long as an add and overlaps with nothing.
-    auto convert_pair = [&](floatx16 (&sc)[2], int e, float &sum) __attribute__((always_inline)) {
+    auto convert_pair = [&](floatx16 (&sc)[2], int e, float &sum, int rb) __attribute__((always_inline)) {
         floatx2 x;
         x[0] = __builtin_amdgcn_exp2f(sc[e / 16][e % 16]);
         x[1] = __builtin_amdgcn_exp2f(sc[(e + 1) / 16][(e + 1) % 16]);
         const bf16x2 pr = __builtin_convertvector(x, bf16x2);
-        pf[e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, pr);
+        pf[rb][e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, pr);
         sum += x[0] + x[1];
         asm volatile("" : "+v"(sum));      // keeps the two additions in this slice (they would be collected behind the last one)
     };
 
     // The exponentials are the vector ALU's heaviest load, so they are split between the two phases: phase B of
     // step i-1 converts scores 0..15 of tile i (right after it has found the tile's max), phase A of step i
-    // converts scores 16..31.
+    // converts scores 16..31.  A slice is one K or V fragment's worth of matrix instructions (one per row block).
     //
     // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next, and spread
     // the copy of the next tile's V (tile `v_tile` into V buffer `v_buf`) over the slices: issued back to back after
-    // a barrier, the copies of all the waves queue up in the texture path.
-    auto phase_a = [&](auto has_next_tag, auto full_tag, int kbuf, floatx16 (&sc)[2], floatx16 (&s_next)[2], int v_tile, int v_buf, int v_cur) __attribute__((always_inline)) {
+    // a barrier, the copies of all the waves queue up in the texture path.  v_cur: V buffer of the current tile.
+    auto phase_a = [&](auto has_next_tag, auto full_tag, int kbuf, floatx16 (&sc)[RBW][2], floatx16 (&s_next)[RBW][2], int v_tile, int v_buf, int v_cur) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;     // the tile being copied is a full prefix tile
-        constexpr int EVERY = NQK / 8;              // one pair of scores every EVERY slices
-        float sum = 0.f;
+        constexpr int PAIRS = 8 * RBW;              // pairs of scores converted here; pair q goes into slice q*NQK/PAIRS
+        float sum[RBW];
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) sum[rb] = 0.f;
         bf16x8 kf[NQK];
         if (HAS_NEXT) {
 #pragma unroll
@@ -460,75 +534,107 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
 #pragma unroll
         for (int idx = 0; idx < NQK; ++idx) {
             if (HAS_NEXT) {
-                s_next[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[idx], qf[idx >> 1], idx < 2 ? m_vec : s_next[idx & 1], 0, 0, 0);
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb)
+                    score_mfma(s_next[rb][idx & 1], kf[idx], rb, idx);
                 if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
                 else vpre[idx + 4 - NQK] = v_frag(v_cur, idx + 4 - NQK);   // phase B's first reads, ahead of the barrier
                 if (idx % (NQK / IPW) == 1) {
-                    if (FULL) dma_v_one_full(v_tile, v_buf, idx / (NQK / IPW));
+                    if (FULL) dma_v_one_full(v_buf, idx / (NQK / IPW));
                     else dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
                 }
             }
-            if (idx % EVERY == 0) convert_pair(sc, 16 + 2 * (idx / EVERY), sum);
+#pragma unroll
+            for (int q = 0; q < PAIRS; ++q)
+                if ((q * NQK) / PAIRS == idx) convert_pair(sc[q % RBW], 16 + 2 * (q / RBW), sum[q % RBW], q % RBW);
             GSD_SLICE_END();
         }
         // keep the conversions in this phase: without a use here the compiler sinks them next to their first use in
         // phase B, behind the barrier, and the overlap with the matrix pipe is lost
-        asm volatile("" : "+v"(pf[2]), "+v"(pf[3]), "+v"(sum));
-        if (HAS_NEXT) asm volatile("" : "+v"(s_next[0]), "+v"(s_next[1]));
-        l_run += sum;
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+            asm volatile("" : "+v"(pf[rb][2]), "+v"(pf[rb][3]), "+v"(sum[rb]));
+            if (HAS_NEXT) asm volatile("" : "+v"(s_next[rb][0]), "+v"(s_next[rb][1]));
+            l_run[rb] += sum[rb];
+        }
     };
 
     // phase B.  vbuf: V buffer of the current tile.  HAS_NEXT: meanwhile the vector ALU masks s_next if `next_tile`
     // is not a full prefix tile, reduces its max (first quarter of the slices), updates the running max and the
-    // running sum, and converts scores 0..15 (second half of the slices; pf[0] and pf[1] have been consumed by then).
+    // running sum, and converts scores 0..15 (later slices; pf[0] and pf[1] have been consumed by then).
     // COPY_K spreads the copy of tile `k_tile` into K buffer `k_buf` over the slices.
-    auto phase_b = [&](auto has_next_tag, auto copy_k_tag, auto full_tag, int vbuf, floatx16 (&s_next)[2], int next_tile, int k_tile, int k_buf, bool k_ahead, int k_next_buf) __attribute__((always_inline)) {
+    auto phase_b = [&](auto has_next_tag, auto copy_k_tag, auto full_tag, int vbuf, floatx16 (&s_next)[RBW][2], int next_tile, int k_tile, int k_buf, bool k_ahead, int k_next_buf) __attribute__((always_inline)) {
         constexpr bool COPY_K = decltype(copy_k_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr int MAX_SLICES = NPV / 4;             // slices that reduce the max
-        constexpr int MAX_PER_SLICE = 16 / MAX_SLICES;  // max3 operations (pairs of scores) in each of them
-        constexpr int CONV_FIRST = NPV / 2;             // first slice that converts
-        constexpr int CONV_PER_SLICE = 8 / (NPV / 2);   // pairs converted per slice
+        constexpr int MAX_PER_SLICE = 16 / MAX_SLICES;  // max3 operations (pairs of scores) per row block in each of them
+        constexpr int CONV_FIRST = MAX_SLICES + 2;      // first slice that converts (decision and fix-up come before)
+        constexpr int PAIRS = 8 * RBW;                  // pair q goes into slice CONV_FIRST + q*(NPV - CONV_FIRST)/PAIRS
+        // pf[.][0] is last read by slice MBD-1 and pf[.][1] by slice 2*MBD-1; they may be rewritten only after that
+        static_assert(CONV_FIRST >= MBD && CONV_FIRST + ((PAIRS / 2) * (NPV - CONV_FIRST)) / PAIRS >= 2 * MBD,
+                      "probabilities of the current tile would be overwritten before they are used");
         bf16x8 vf[NPV];
 #pragma unroll
         for (int x = 0; x < 4; ++x) vf[x] = vpre[x];
-        if (HAS_NEXT && !FULL && next_tile >= full_end) apply_mask(s_next, next_tile);   // FULL: the next tile is a full prefix tile too
-        float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
-        float sum = 0.f;
+        if (ASM_MFMA && HAS_NEXT) mfma_settle();            // the scores written by phase A's last matrix instructions
+        if (HAS_NEXT && !FULL && next_tile >= full_end) {   // FULL: the next tile is a full prefix tile too
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) apply_mask(s_next[rb], next_tile, rb);
+        }
+        float mx0[RBW], mx1[RBW], sum[RBW];
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
+            mx0[rb] = -__builtin_inff();
+            mx1[rb] = -__builtin_inff();
+            sum[rb] = 0.f;
+        }
         GSD_SLICE_END();
 #pragma unroll
         for (int idx = 0; idx < NPV; ++idx) {
             const int ks2 = idx / MBD, mbd = idx % MBD;
-            acc_o[mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, pf[ks2]), acc_o[mbd], 0, 0, 0);
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb)
+                if (ASM_MFMA) mfma_a_acc(acc_o[rb][mbd], vf[idx], __builtin_bit_cast(bf16x8, pf[rb][ks2]));
+                else acc_o[rb][mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, pf[rb][ks2]), acc_o[rb][mbd], 0, 0, 0);
             if (idx + 4 < NPV) vf[idx + 4] = v_frag(vbuf, idx + 4);
             else if (HAS_NEXT && k_ahead) kpre[idx + 4 - NPV] = k_frag(k_next_buf, idx + 4 - NPV);   // next phase A's first reads
             if (COPY_K && idx % (NPV / IPW) == 1) {
-                if (FULL) dma_k_one_full(k_tile, k_buf, idx / (NPV / IPW));
+                if (FULL) dma_k_one_full(k_buf, idx / (NPV / IPW));
                 else dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
             }
             if (HAS_NEXT) {
                 if (idx < MAX_SLICES) {
 #pragma unroll
-                    for (int x = 0; x < MAX_PER_SLICE; ++x) {
-                        const int e = 2 * (idx * MAX_PER_SLICE + x);
-                        if (x & 1) mx1 = max3(mx1, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
-                        else mx0 = max3(mx0, s_next[e / 16][e % 16], s_next[(e + 1) / 16][(e + 1) % 16]);
-                    }
-                }
-                if (idx == MAX_SLICES) decide_max(fmaxf(mx0, mx1));
-                if (idx == CONV_FIRST - 1) apply_max(s_next);
-                if (idx >= CONV_FIRST) {
+                    for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
-                    for (int x = 0; x < CONV_PER_SLICE; ++x)
-                        convert_pair(s_next, 2 * ((idx - CONV_FIRST) * CONV_PER_SLICE + x), sum);
+                        for (int x = 0; x < MAX_PER_SLICE; ++x) {
+                            const int e = 2 * (idx * MAX_PER_SLICE + x);
+                            if (x & 1) mx1[rb] = max3(mx1[rb], s_next[rb][e / 16][e % 16], s_next[rb][(e + 1) / 16][(e + 1) % 16]);
+                            else mx0[rb] = max3(mx0[rb], s_next[rb][e / 16][e % 16], s_next[rb][(e + 1) / 16][(e + 1) % 16]);
+                        }
                 }
+                if (idx == MAX_SLICES) {
+#pragma unroll
+                    for (int rb = 0; rb < RBW; ++rb) decide_max(fmaxf(mx0[rb], mx1[rb]), rb);
+                }
+                if (idx == MAX_SLICES + 1) {
+#pragma unroll
+                    for (int rb = 0; rb < RBW; ++rb) apply_max(s_next[rb], rb);
+                }
+#pragma unroll
+                for (int q = 0; q < PAIRS; ++q)
+                    if (CONV_FIRST + (q * (NPV - CONV_FIRST)) / PAIRS == idx)
+                        convert_pair(s_next[q % RBW], 2 * (q / RBW), sum[q % RBW], q % RBW);
             }
             GSD_SLICE_END();
         }
         if (HAS_NEXT) {
-            asm volatile("" : "+v"(pf[0]), "+v"(pf[1]), "+v"(sum));
-            l_run += sum;
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) {
+                asm volatile("" : "+v"(pf[rb][0]), "+v"(pf[rb][1]), "+v"(sum[rb]));
+                l_run[rb] += sum[rb];
+            }
         }
     };
 
@@ -538,7 +644,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
     int c0 = next_live(t_begin - 1);
     if (c0 < t_end) {
         int c1 = next_live(c0), c2 = next_live(c1), c3 = next_live(c2);
-        floatx16 sa[2], sb[2];
+        floatx16 sa[RBW][2], sb[RBW][2];
         // prologue: K(0), V(0), K(1) on their way; scores and max of tile 0; then V(1), K(2)
         dma_k(c0, 0);
         dma_v(c0, 0);
@@ -549,22 +655,24 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             dma_wait<0>();
         }
         wg_barrier();
-        {
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) {
 #pragma unroll
             for (int idx = 0; idx < NQK; ++idx)
-                sa[idx & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(0, idx), qf[idx >> 1], idx < 2 ? m_vec : sa[idx & 1], 0, 0, 0);
-            if (c0 >= full_end) apply_mask(sa, c0);
-            float mx = sa[0][0];
+                score_mfma(sa[rb][idx & 1], k_frag(0, idx), rb, idx);
+            if (ASM_MFMA) mfma_settle();
+            if (c0 >= full_end) apply_mask(sa[rb], c0, rb);
+            float mx = sa[rb][0][0];
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sa[mb][j]);
-            decide_max(mx);
-            apply_max(sa);
+                for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sa[rb][mb][j]);
+            decide_max(mx, rb);
+            apply_max(sa[rb], rb);
             float sum = 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; e += 2) convert_pair(sa, e, sum);
-            l_run += sum;
+            for (int e = 0; e < 16; e += 2) convert_pair(sa[rb], e, sum, rb);
+            l_run[rb] += sum;
         }
         wg_barrier();          // K buffer 0 has been read by every wave
         if (c2 < t_end) {
@@ -583,7 +691,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         // one step with the current scores in `cur`, leaving the next tile's scores in `nxt`.  STEADY: tiles
         // i+2 and i+3 exist, so nothing in the step is conditional and two copies stay in flight at each wait.
         // FAST: all tiles up to i+4 are full prefix tiles: no search for the next live tile, no clamp in the copies.
-        auto step = [&](auto steady_tag, auto fast_tag, floatx16 (&cur)[2], floatx16 (&nxt)[2]) __attribute__((always_inline)) {
+        auto step = [&](auto steady_tag, auto fast_tag, floatx16 (&cur)[RBW][2], floatx16 (&nxt)[RBW][2]) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;
             constexpr bool FAST = decltype(fast_tag)::value;
             rescale();
@@ -598,6 +706,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
             ++i;
         };
         // steady state over the prefix, two steps per trip so that the two score buffers swap roles without copies
+        if (c3 + 2 < full_end) start_full_run(c3, c1);
         while (c3 + 2 < full_end) {
             step(True{}, True{}, sa, sb);
             step(True{}, True{}, sb, sa);
@@ -605,12 +714,16 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
         while (c3 < t_end) {       // the rest of the steady state: the next live tile has to be searched for
             step(True{}, False{}, sa, sb);
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) sa[mb] = sb[mb];
+            for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) sa[rb][mb] = sb[rb][mb];
         }
         while (c1 < t_end) {       // the last steps: no more tiles to prefetch
             step(False{}, False{}, sa, sb);
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) sa[mb] = sb[mb];
+            for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) sa[rb][mb] = sb[rb][mb];
         }
         // last tile: nothing left to prefetch or to score
         rescale();
@@ -620,40 +733,46 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void dag_attention_bf16_kernel(con
 
     // ---- epilogue ------------------------------------------------------------------------------------------
     // accumulator register i of channel block mbd is channel  mbd*32 + 8*(i/4) + 4*half + i%4
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    if (!row_valid) return;
-    if (p.splits == 1) {
-        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        __bf16 *op = p.o + t * p.o_ts + int64_t(head) * p.o_hs + 4 * half;
+    if (ASM_MFMA) mfma_settle();
 #pragma unroll
-        for (int mbd = 0; mbd < MBD; ++mbd)
+    for (int rb = 0; rb < RBW; ++rb) {
+        const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32, 64);
+        if (!row_is_valid(rb)) continue;
+        const int64_t t = int64_t(node_base) + node_of(rb);
+        const int32_t head = head_of(rb);
+        if (p.splits == 1) {
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            __bf16 *op = p.o + t * p.o_ts + int64_t(head) * p.o_hs + 4 * half;
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                bf16x4 x;
+            for (int mbd = 0; mbd < MBD; ++mbd)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc_o[mbd][i4 * 4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(op + mbd * 32 + i4 * 8) = x;
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    bf16x4 x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc_o[rb][mbd][i4 * 4 + e] * inv);
+                    *reinterpret_cast<bf16x4 *>(op + mbd * 32 + i4 * 8) = x;
+                }
+            if (p.lse && half == 0)
+                p.lse[t * p.num_q_heads + head] =
+                    l_tot > 0.f ? (m_run[rb] + __log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
+        } else {
+            const int64_t prow = (int64_t(split) * p.total_nodes + t) * p.num_q_heads + head;
+            float *op = p.part_o + prow * D + 4 * half;
+#pragma unroll
+            for (int mbd = 0; mbd < MBD; ++mbd)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    floatx4 x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = acc_o[rb][mbd][i4 * 4 + e];
+                    *reinterpret_cast<floatx4 *>(op + mbd * 32 + i4 * 8) = x;
+                }
+            if (half == 0) {
+                floatx2 ml;
+                ml[0] = l_tot > 0.f ? m_run[rb] : kMInit;
+                ml[1] = l_tot;
+                *reinterpret_cast<floatx2 *>(p.part_ml + prow * 2) = ml;
             }
-        if (p.lse && half == 0)
-            p.lse[t * p.num_q_heads + head] =
-                l_tot > 0.f ? (m_run + __log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
-    } else {
-        const int64_t prow = (int64_t(split) * p.total_nodes + t) * p.num_q_heads + head;
-        float *op = p.part_o + prow * D + 4 * half;
-#pragma unroll
-        for (int mbd = 0; mbd < MBD; ++mbd)
-#pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                floatx4 x;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) x[e] = acc_o[mbd][i4 * 4 + e];
-                *reinterpret_cast<floatx4 *>(op + mbd * 32 + i4 * 8) = x;
-            }
-        if (half == 0) {
-            floatx2 ml;
-            ml[0] = l_tot > 0.f ? m_run : kMInit;
-            ml[1] = l_tot;
-            *reinterpret_cast<floatx2 *>(p.part_ml + prow * 2) = ml;
         }
     }
 }
@@ -692,16 +811,23 @@ __global__ __launch_bounds__(256) void dag_attention_combine_kernel(const AttnPa
 
 // ---------------------------------------------------------------------------------------------- host side
 
-// wavefronts per work-group: 8 (256-row tiles) when a (sequence, KV head) can fill them, else 4
-static int waves_of(const gsd_attn_desc &d) {
-    if (d.wg_waves == 4 || d.wg_waves == 8) return d.wg_waves;
+// Shape of a work-group: (wavefronts, 32-row blocks per wavefront).  256-row tiles (8 waves x 1 block) when a
+// (sequence, KV head) can fill them, else 128-row tiles (4 x 1).  gsd_attn_desc.wg_waves overrides: 4 -> 4 x 1,
+// 8 -> 8 x 1, 64 -> 4 x 2 (measured slower: with one wave per SIMD nothing fills a wave's issue stalls).
+struct WgShape { int waves, blocks; };
+static WgShape shape_of(const gsd_attn_desc &d) {
+    if (d.wg_waves == 4) return {4, 1};
+    if (d.wg_waves == 8) return {8, 1};
+    if (d.wg_waves == 64) return {4, 2};
     const int group = d.num_q_heads / d.num_kv_heads;
-    return d.max_nodes * group >= 256 ? 8 : 4;
+    return d.max_nodes * group >= 256 ? WgShape{8, 1} : WgShape{4, 1};
 }
+static int waves_of(const gsd_attn_desc &d) { return shape_of(d).waves; }
 
 static int q_tiles_of(const gsd_attn_desc &d) {
     const int group = d.num_q_heads / d.num_kv_heads;
-    const int rows_per_wg = waves_of(d) * 32;
+    const WgShape sh = shape_of(d);
+    const int rows_per_wg = sh.waves * sh.blocks * 32;
     return (d.max_nodes * group + rows_per_wg - 1) / rows_per_wg;
 }
 
@@ -744,16 +870,17 @@ hipError_t launch_attention_bf16(const gsd_attn_desc &d, int splits, hipStream_t
     p.scale = d.softmax_scale;
     p.scale_log2e = d.softmax_scale * kLog2e;
 
-    const int nw = waves_of(d);
-    const dim3 grid(p.wg_per_xcd * 8), block(nw * 64);
-    if (d.head_dim == 128 && nw == 8)
-        hipLaunchKernelGGL((dag_attention_bf16_kernel<128, 8>), grid, block, 0, stream, p);
-    else if (d.head_dim == 128)
-        hipLaunchKernelGGL((dag_attention_bf16_kernel<128, 4>), grid, block, 0, stream, p);
-    else if (nw == 8)
-        hipLaunchKernelGGL((dag_attention_bf16_kernel<64, 8>), grid, block, 0, stream, p);
-    else
-        hipLaunchKernelGGL((dag_attention_bf16_kernel<64, 4>), grid, block, 0, stream, p);
+    const WgShape sh = shape_of(d);
+    const dim3 grid(p.wg_per_xcd * 8), block(sh.waves * 64);
+    if (d.head_dim == 128) {
+        if (sh.blocks == 2) hipLaunchKernelGGL((dag_attention_bf16_kernel<128, 4, 2>), grid, block, 0, stream, p);
+        else if (sh.waves == 8) hipLaunchKernelGGL((dag_attention_bf16_kernel<128, 8, 1>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((dag_attention_bf16_kernel<128, 4, 1>), grid, block, 0, stream, p);
+    } else {
+        if (sh.blocks == 2) hipLaunchKernelGGL((dag_attention_bf16_kernel<64, 4, 2>), grid, block, 0, stream, p);
+        else if (sh.waves == 8) hipLaunchKernelGGL((dag_attention_bf16_kernel<64, 8, 1>), grid, block, 0, stream, p);
+        else hipLaunchKernelGGL((dag_attention_bf16_kernel<64, 4, 1>), grid, block, 0, stream, p);
+    }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     if (splits > 1) {

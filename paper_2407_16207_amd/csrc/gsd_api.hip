@@ -40,8 +40,8 @@ int check_attn_desc(const gsd_attn_desc *d) {
         return fail(GSD_ERR_INVALID_ARG, "words_per_row %d too small for max_nodes %d", d->words_per_row,
                     d->max_nodes);
     if (d->num_splits < 0) return fail(GSD_ERR_INVALID_ARG, "num_splits must be >= 0");
-    if (d->wg_waves != 0 && d->wg_waves != 4 && d->wg_waves != 8)
-        return fail(GSD_ERR_INVALID_ARG, "wg_waves must be 0, 4 or 8");
+    if (d->wg_waves != 0 && d->wg_waves != 4 && d->wg_waves != 8 && d->wg_waves != 64)
+        return fail(GSD_ERR_INVALID_ARG, "wg_waves must be 0, 4, 8 or 64");
     if (!(d->softmax_scale > 0.f) || !(d->softmax_scale < 1e6f))
         return fail(GSD_ERR_INVALID_ARG, "softmax_scale must be positive and finite");
     return GSD_OK;

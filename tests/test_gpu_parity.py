@@ -153,7 +153,7 @@ def test_attention_fp32_general(gpu, ref, D):
     check_attention(gpu, ref, w)
 
 
-@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("waves", [4, 8, 64])
 @pytest.mark.parametrize("splits", [1, 2, 3, 7])
 @pytest.mark.parametrize("D", [128, 64])
 def test_attention_bf16_small_all_rows(gpu, ref, D, splits, waves):
