@@ -1,5 +1,6 @@
-"""CPU oracle of the steps around the verify pass: un-merging the token graph into a token tree (Section 5.4)
-and committing the accepted path to the KV cache (the cache update of Section 6.5).  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle of the steps around the verify pass: un-merging the token graph into a token tree (Section 5.4),
+committing the accepted path to the KV cache (the cache update of Section 6.5) and non-deterministic verification
+(Sections 3 and 6.4).  TEST INFRASTRUCTURE ONLY.
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module; the product path never
 does.  Plain Python / numpy, written from the definitions; it shares nothing with the HIP path.
@@ -84,3 +85,92 @@ def commit_kv(k, v, kv_offsets, prefix_lens, accept_len, accept_path):
             new_v[:, base + j] = v[:, src]
         new_len[b] += int(accept_len[b])
     return new_k, new_v, new_len
+
+
+# ------------------------------------------------------------------------------------------ non-deterministic
+def softmax_rows(logits):
+    """Row-wise softmax in fp64 of stored (fp32 or bf16-bits) logits; returns (probabilities, row max, sum of exp)."""
+    x = np.asarray(logits)
+    if x.dtype == np.uint16:
+        x = (x.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    x = x.astype(np.float64)
+    m = x.max(axis=1, keepdims=True)
+    e = np.exp(x - m)
+    z = e.sum(axis=1, keepdims=True)
+    return e / z, m[:, 0], z[:, 0]
+
+
+def accept_stochastic(node_offsets, parent_offsets, parent_idx, tokens, p_nodes, p_root, draft_prob, accept_u,
+                      q_nodes, q_root, resample_u, max_nodes=None):
+    """Non-deterministic verification (Section 3; Section 6.4 gives no rule for several hypotheses, so the reading
+    is stated here).  p_nodes[T, V] / p_root[B, V]: the LLM's next-token distribution after each node / after the
+    context; q_nodes, q_root: the draft model's.  draft_prob[i]: the probability the draft model gave token i when
+    it drafted node i; accept_u[i], resample_u[b]: uniforms in [0, 1).
+
+      * an edge r -> i is accepted iff accept_u[i] < min(1, p_r(token_i) / draft_prob[i])   (one coin per node);
+      * a root path is accepted iff all its edges are; the longest accepted root path is taken, with the
+        deterministic rule's tie-breaks (smallest end node, then smallest qualifying parent);
+      * the LLM then "regenerates" one token after the path's end r*: if r* has children in the graph (they were all
+        rejected or not on a longer accepted path) it is drawn from the residual distribution max(p - q, 0) at r*,
+        normalised (from p itself if the residual is empty), and from p if r* has no children; the draw is by
+        inverse CDF: the smallest token x whose cumulative weight exceeds resample_u * total.
+
+    Returns (accept_len[B], accept_path[B, max_nodes], bonus_token[B], edge_ok[E] bool, resid_cdf: list of [V] fp64)."""
+    node_offsets = np.asarray(node_offsets, dtype=np.int64)
+    parent_offsets = np.asarray(parent_offsets, dtype=np.int64)
+    parent_idx = np.asarray(parent_idx, dtype=np.int64)
+    B = len(node_offsets) - 1
+    nmax = int(np.max(np.diff(node_offsets))) if B else 0
+    max_nodes = max(1, nmax) if max_nodes is None else int(max_nodes)
+    accept_len = np.zeros(B, dtype=np.int32)
+    accept_path = np.full((B, max_nodes), -1, dtype=np.int32)
+    bonus = np.zeros(B, dtype=np.int32)
+    edge_ok = np.zeros(len(parent_idx), dtype=bool)
+    cdfs = []
+    for b in range(B):
+        lo, hi = int(node_offsets[b]), int(node_offsets[b + 1])
+        n = hi - lo
+        L = [-1] * n
+        back = [None] * n
+        has_child = [False] * n
+        root_has_child = False
+        for i in range(n):
+            tok = int(tokens[lo + i])
+            for e in range(int(parent_offsets[lo + i]), int(parent_offsets[lo + i + 1])):
+                r = int(parent_idx[e])
+                if r < -1 or r >= i:
+                    continue
+                if r == -1:
+                    root_has_child = True
+                else:
+                    has_child[r] = True
+                p_tok = p_root[b, tok] if r == -1 else p_nodes[lo + r, tok]
+                ok = accept_u[lo + i] < min(1.0, p_tok / draft_prob[lo + i])
+                edge_ok[e] = ok
+                lr = 0 if r == -1 else L[r]
+                if ok and lr >= 0 and (lr + 1 > L[i] or (lr + 1 == L[i] and r < back[i])):
+                    L[i] = lr + 1
+                    back[i] = r
+        best, end = 0, -1
+        for i in range(n):
+            if L[i] > best:
+                best, end = L[i], i
+        accept_len[b] = best
+        v = end
+        for pos in range(best - 1, -1, -1):
+            accept_path[b, pos] = v
+            v = back[v]
+        p_end = p_root[b] if end == -1 else p_nodes[lo + end]
+        q_end = q_root[b] if end == -1 else q_nodes[lo + end]
+        rejected_some = root_has_child if end == -1 else has_child[end]
+        w = np.maximum(p_end - q_end, 0.0) if rejected_some else p_end.copy()
+        if w.sum() <= 0.0:
+            w = p_end.copy()
+        cdf = np.cumsum(w)
+        cdfs.append(cdf)
+        target = resample_u[b] * cdf[-1]
+        x = int(np.searchsorted(cdf, target, side="right"))
+        if x >= len(cdf):                       # target == total by rounding: the last token that carries weight
+            x = int(np.flatnonzero(w > 0)[-1])
+        bonus[b] = x
+    return accept_len, accept_path, bonus, edge_ok, cdfs

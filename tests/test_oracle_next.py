@@ -191,3 +191,97 @@ def test_commit_equals_appending_only_the_accepted_tokens():
             assert np.array_equal(new[:, base + nl[b]:base + P + n_draft], old[:, base + nl[b]:base + P + n_draft])
     assert np.array_equal(nk[:, kv_offsets[1]:kv_offsets[2]], k[:, kv_offsets[1]:kv_offsets[2]])
     assert np.array_equal(nk[:, kv_offsets[2]:], k[:, kv_offsets[2]:])      # identity path: no change at all
+
+
+# ----------------------------------------------------------------------------------- non-deterministic verify
+def tiny_problem(rng, n, vocab, peaked=False):
+    off, par = random_dag(rng, n, max_parents=2, p_root=0.3)
+    tokens = rng.integers(0, vocab, n).astype(np.int32)
+    lp = rng.standard_normal((n + 1, vocab)) * (8.0 if peaked else 1.0)
+    lq = rng.standard_normal((n + 1, vocab))
+    p, _, _ = gsd_next.softmax_rows(lp.astype(np.float32))
+    q, _, _ = gsd_next.softmax_rows(lq.astype(np.float32))
+    return off, par, tokens, p, q
+
+
+def run_stochastic(off, par, tokens, p, q, draft_prob, u, w):
+    n = len(off) - 1
+    return gsd_next.accept_stochastic([0, n], off, par, tokens, p[:n], p[n:], draft_prob, u, q[:n], q[n:], [w])
+
+
+def test_softmax_rows_is_the_library_softmax():
+    import torch
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((5, 37)).astype(np.float32) * 3
+    p, m, z = gsd_next.softmax_rows(x)
+    want = torch.softmax(torch.from_numpy(x).double(), dim=1).numpy()
+    assert np.abs(p - want).max() < 1e-15
+    assert np.allclose(m, x.max(axis=1)) and np.allclose(np.log(z) + m, torch.logsumexp(torch.from_numpy(x).double(), 1).numpy())
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_limits_of_the_acceptance_test(ref, seed):
+    rng = np.random.default_rng(4000 + seed)
+    n, vocab = int(rng.integers(1, 14)), 5
+    off, par, tokens, p, q = tiny_problem(rng, n, vocab)
+    u = rng.random(n)
+    # a draft that never over-estimates (draft_prob <= every p it is compared with): every edge passes, the longest
+    # root path of the graph is accepted
+    ln, path, _, ok, _ = run_stochastic(off, par, tokens, p, q, np.full(n, 1e-9), u, 0.5)
+    assert ok[[e for i in range(n) for e in range(off[i], off[i + 1])]].all()
+    depth = max(len(pth) for pth in all_root_paths(n, off, par))
+    assert ln[0] == depth
+    # coins at 1 - eps against a draft that is always over-confident: nothing passes
+    ln, path, bonus, ok, _ = run_stochastic(off, par, tokens, p * 0.5, q, np.ones(n), np.full(n, 0.999), 0.5)
+    assert ln[0] == 0 and (path == -1).all() and not ok.any()
+    # a (nearly) one-hot LLM against a draft that was certain: the test degenerates to "token == the LLM's token",
+    # i.e. to deterministic verification
+    lp = np.full((n + 1, vocab), -60.0)
+    pred = rng.integers(0, vocab, n + 1)
+    lp[np.arange(n + 1), pred] = 0.0
+    p1, _, _ = gsd_next.softmax_rows(lp.astype(np.float32))
+    ln, path, bonus, _, _ = run_stochastic(off, par, tokens, p1, p1 * 0, np.ones(n), u * 0.999, 0.3)
+    dl, dpath, dbonus = ref.accept_longest_path([0, n], off, par, tokens, pred[:n].astype(np.int32), [int(pred[n])])
+    assert ln[0] == dl[0] and np.array_equal(path[0, :ln[0]], dpath[0, :dl[0]])
+    assert bonus[0] == dbonus[0]            # q = 0: the residual is p itself, whose mass sits on the LLM's token
+
+
+def test_hand_example_chain_of_two():
+    # root -> 0 -> 1, vocabulary {0,1,2}
+    off, par = chain_dag(2)
+    tokens = np.array([1, 2], dtype=np.int32)
+    p = np.array([[0.2, 0.3, 0.5],      # after node 0
+                  [0.1, 0.1, 0.8],      # after node 1
+                  [0.6, 0.3, 0.1]])     # after the context
+    q = np.array([[0.1, 0.1, 0.8],
+                  [0.3, 0.3, 0.4],
+                  [0.2, 0.6, 0.2]])
+    draft_prob = np.array([0.6, 0.8])   # q_root(1), q_0(2)
+    # edge root->0: ratio 0.3/0.6 = 0.5; edge 0->1: 0.5/0.8 = 0.625
+    ln, path, bonus, ok, cdfs = run_stochastic(off, par, tokens, p, q, draft_prob, np.array([0.49, 0.7]), 0.5)
+    assert ok.tolist() == [True, False] and ln[0] == 1 and path[0, 0] == 0
+    # rejection after node 0: residual max(p0 - q0, 0) = [0.1, 0.2, 0] -> cdf [0.1, 0.3, 0.3]; 0.5 * 0.3 = 0.15 -> token 1
+    assert np.allclose(cdfs[0], [0.1, 0.3, 0.3]) and bonus[0] == 1
+    ln, path, bonus, ok, cdfs = run_stochastic(off, par, tokens, p, q, draft_prob, np.array([0.51, 0.1]), 0.9)
+    # first edge rejected: everything after it is discarded; residual at the root max(p - q, 0) = [0.4, 0, 0] -> token 0
+    assert ln[0] == 0 and bonus[0] == 0
+    ln, path, bonus, ok, cdfs = run_stochastic(off, par, tokens, p, q, draft_prob, np.array([0.1, 0.1]), 0.15)
+    # both accepted; node 1 is a leaf: the next token is drawn from p_1 = [0.1, 0.1, 0.8]: 0.15 -> token 1
+    assert ln[0] == 2 and path[0, :2].tolist() == [0, 1] and bonus[0] == 1
+
+
+def test_first_emitted_token_is_distributed_as_the_llm_says():
+    """The classic guarantee of speculative sampling (the reason for the min(1, p/q) test and the residual draw): with
+    the drafted token SAMPLED from q, the token emitted at that position is distributed exactly as p."""
+    rng = np.random.default_rng(12)
+    vocab, trials = 4, 40000
+    p = np.array([[0.1, 0.2, 0.3, 0.4], [0.25, 0.25, 0.25, 0.25]])      # row 0: after node 0 (unused), row 1: after the context
+    q = np.array([[0.25, 0.25, 0.25, 0.25], [0.55, 0.05, 0.3, 0.1]])
+    off, par = chain_dag(1)
+    counts = np.zeros(vocab)
+    for _ in range(trials):
+        tok = int(rng.choice(vocab, p=q[1]))
+        ln, path, bonus, _, _ = gsd_next.accept_stochastic([0, 1], off, par, np.array([tok]), p[:1], p[1:], np.array([q[1, tok]]),
+                                                           rng.random(1), q[:1], q[1:], rng.random(1))
+        counts[tok if ln[0] == 1 else bonus[0]] += 1
+    assert np.abs(counts / trials - p[1]).max() < 4 * np.sqrt(0.25 / trials)     # four standard errors
