@@ -197,6 +197,42 @@ def bench_unmerge(gsd, w, dev, stream, reps=20):
             "attention_cost_ratio_tree_over_graph": {"flops": tree_flops / dag_flops, "time": tree_ms / dag_ms}}
 
 
+def bench_stochastic(gsd, w, dev, logits, stream, reps=20):
+    """Non-deterministic verification on the step's graphs: the LLM's logits are the workload's, the draft model's
+    logits are a second seeded draw of the same shape; reports the vocabulary-wide normaliser pass against HBM."""
+    import numpy as np
+    import torch
+    cfg = w.cfg
+    T, B, V = w.total_nodes, cfg.batch, cfg.vocab
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed + 17)
+    draft_logits = torch.randn((T, V), generator=g, device="cuda", dtype=torch.float32).to(logits.dtype)
+    root_logits = torch.randn((B, V), generator=g, device="cuda", dtype=torch.float32).to(logits.dtype)
+    root_draft = torch.randn((B, V), generator=g, device="cuda", dtype=torch.float32).to(logits.dtype)
+    draft_prob = torch.rand(T, generator=g, device="cuda") * 2e-4 + 1e-5          # of the order of 1/vocab
+    accept_u = torch.rand(T, generator=g, device="cuda")
+    resample_u = torch.rand(B, generator=g, device="cuda")
+    no, po, pi, tok = dev(w.node_offsets), dev(w.parent_offsets), dev(w.parent_idx), dev(w.tokens)
+    row_max = torch.empty(T, dtype=torch.float32, device="cuda")
+    row_sum = torch.empty(T, dtype=torch.float32, device="cuda")
+    stats_ms = time_launches(stream, lambda i: gsd.gsd_softmax_stats(logits, row_max, row_sum), reps)
+    res = None
+
+    def whole(i):
+        nonlocal res
+        res = gsd.gsd_accept_stochastic(no, po, pi, tok, logits, root_logits, draft_logits, root_draft, draft_prob,
+                                        accept_u, resample_u, w.max_nodes)
+    total_ms = time_launches(stream, whole, reps)
+    nbytes = float(T) * V * logits.element_size()
+    gbs = nbytes / (stats_ms * 1e-3) / 1e9
+    return {"softmax_stats": {"kernel": "softmax_stats_kernel", "bound": "hbm", "algorithmic_bytes_per_launch": nbytes,
+                              "avg_launch_ms": stats_ms, "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": gbs / HBM_PEAK_GBS},
+            "accept_stochastic_ms": total_ms, "accepted_lengths": res[0].cpu().tolist(),
+            "note": "whole call = normaliser passes over node and root logits + acceptance + residual draw "
+                    "(includes the binding's output allocations)"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -414,6 +450,7 @@ def main():
         result["kv_commit"] = bench_commit_kv(gsd, w, kv_offsets, prefix_lens, accept_len, accept_path, stream,
                                               args.cache_layers)
         result["unmerge_to_tree"] = bench_unmerge(gsd, w, dev, stream)
+        result["stochastic_verify"] = bench_stochastic(gsd, w, dev, logits, stream)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_nodes)
         result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]

@@ -11,6 +11,7 @@
  * and, around that pass,
  *   gsd_unmerge_to_tree       token graph -> token tree with replicated successors (Section 5.4), gsd_gather_rows
  *   gsd_commit_kv             accepted path -> contiguous context rows of the KV cache (Section 6.5)
+ *   gsd_accept_stochastic     non-deterministic verification (Sections 3, 6.4), gsd_softmax_stats
  *
  * Conventions common to all calls
  *   - Every data pointer is a DEVICE pointer owned by the caller; scalars and the descriptor struct are host
@@ -224,6 +225,51 @@ int gsd_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers, int64_t 
                   int64_t token_stride_bytes, int64_t layer_stride_bytes, const int64_t *kv_offsets,
                   const int32_t *prefix_lens, const int32_t *accept_len, const int32_t *accept_path,
                   int32_t *new_prefix_lens, void *hip_stream);
+
+/*
+ * Normaliser of a softmax over each row of logits, in one pass (running maximum and sum of exp(x - max), merged
+ * across lanes): row_max[r] = max_x logits[r][x], row_sumexp[r] = sum_x exp(logits[r][x] - row_max[r]).  The
+ * vocabulary-wide part of non-deterministic verification (Section 3: acceptance needs the LLM's probability
+ * p(token) = exp(logit - max) / sumexp), the counterpart of gsd_node_argmax.  An all -inf row gives (-inf, 0).
+ *   rows >= 1, vocab >= 1, dtype GSD_F32 or GSD_BF16, row_stride in elements; row_max, row_sumexp: [rows] fp32.
+ */
+int gsd_softmax_stats(int64_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride, float *row_max,
+                      float *row_sumexp, void *hip_stream);
+
+/*
+ * Non-deterministic verification on the token graph (Section 3: the i-th drafted token is accepted with probability
+ * min(1, p/q), the first rejection discards the rest of its hypothesis and the LLM regenerates that token; Section
+ * 6.4: the setting on token graphs, for which the paper states no rule of its own).  As built:
+ *   - edge r -> i is accepted iff accept_u[i] < min(1, p_r(tokens[i]) / draft_prob[i]), p_r = softmax of the LLM's
+ *     logits after r (the root's after the context); one coin per node, shared by all its parent edges;
+ *   - the longest accepted root path is taken, ties as in gsd_accept_longest_path;
+ *   - bonus_token is drawn after the path's end node r* by inverse CDF with resample_u[b] (the smallest token whose
+ *     cumulative weight exceeds resample_u * total): from max(p - q, 0) at r* when r* has children in the graph
+ *     (q = softmax of the draft model's logits after r*; p itself if that residual is empty), from p when it has none.
+ * All four logits arrays share dtype, vocab and row_stride (elements).  Malformed parent ids and tokens outside
+ * [0, vocab) never pass.  Launches four kernels on `hip_stream` (two normaliser passes, acceptance, draw).
+ */
+typedef struct gsd_stochastic_desc {
+    int32_t batch, total_nodes, max_nodes, vocab, dtype;
+    const int32_t *node_offsets;    /* [B+1] */
+    const int32_t *parent_offsets;  /* [T+1] */
+    const int32_t *parent_idx;      /* [E]   */
+    const int32_t *tokens;          /* [T]   */
+    const void *logits;             /* [T][vocab] LLM logits after each node */
+    const void *root_logits;        /* [B][vocab] LLM logits after the context */
+    const void *draft_logits;       /* [T][vocab] draft model's logits after each node */
+    const void *root_draft_logits;  /* [B][vocab] */
+    int64_t row_stride;
+    const float *draft_prob;        /* [T] probability the draft model gave tokens[i] when it drafted node i, > 0 */
+    const float *accept_u;          /* [T] uniforms in [0, 1) */
+    const float *resample_u;        /* [B] uniforms in [0, 1) */
+    float *row_max, *row_sumexp;    /* [T+B] out: softmax normalisers of `logits` rows, then of `root_logits` rows */
+    int32_t *accept_len;            /* [B] out */
+    int32_t *accept_path;           /* [B][max_nodes] out, -1 padded */
+    int32_t *end_node;              /* [B] out: last node of the accepted path, -1 = the root */
+    int32_t *bonus_token;           /* [B] out */
+} gsd_stochastic_desc;
+int gsd_accept_stochastic(const gsd_stochastic_desc *desc, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -3,7 +3,7 @@ Speculative Decoding.  Argument marshalling only: torch supplies device memory a
 the path runs in the library's HIP kernels.  There is no CPU fallback; a missing library raises.
 
     gsd_build_mask, gsd_dag_attention, gsd_node_argmax, gsd_accept_longest_path,
-    gsd_unmerge_to_tree, gsd_gather_rows, gsd_commit_kv
+    gsd_unmerge_to_tree, gsd_gather_rows, gsd_commit_kv, gsd_softmax_stats, gsd_accept_stochastic
 
 mirror the C entry points of the same names.
 """
@@ -22,7 +22,7 @@ GSD_MAX_NODES_PER_SEQ = 512
 
 EXPORTS = ("gsd_status_string", "gsd_last_error", "gsd_version", "gsd_build_mask", "gsd_dag_attention_workspace",
            "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_node_argmax", "gsd_accept_longest_path",
-           "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv")
+           "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv", "gsd_softmax_stats", "gsd_accept_stochastic")
 
 
 class GsdError(RuntimeError):
@@ -45,6 +45,20 @@ class AttnDesc(ctypes.Structure):
         ("o_token_stride", ctypes.c_int64), ("o_head_stride", ctypes.c_int64),
         ("kv_token_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+class StochasticDesc(ctypes.Structure):
+    """Mirror of struct gsd_stochastic_desc."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("total_nodes", ctypes.c_int32), ("max_nodes", ctypes.c_int32),
+        ("vocab", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("node_offsets", ctypes.c_void_p), ("parent_offsets", ctypes.c_void_p), ("parent_idx", ctypes.c_void_p),
+        ("tokens", ctypes.c_void_p), ("logits", ctypes.c_void_p), ("root_logits", ctypes.c_void_p),
+        ("draft_logits", ctypes.c_void_p), ("root_draft_logits", ctypes.c_void_p), ("row_stride", ctypes.c_int64),
+        ("draft_prob", ctypes.c_void_p), ("accept_u", ctypes.c_void_p), ("resample_u", ctypes.c_void_p),
+        ("row_max", ctypes.c_void_p), ("row_sumexp", ctypes.c_void_p), ("accept_len", ctypes.c_void_p),
+        ("accept_path", ctypes.c_void_p), ("end_node", ctypes.c_void_p), ("bonus_token", ctypes.c_void_p),
     ]
 
 
@@ -87,6 +101,8 @@ def load_library() -> ctypes.CDLL:
         lib.gsd_unmerge_to_tree.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.gsd_gather_rows.argtypes = [i64, i64, vp, i64, i64, vp, vp, i64, vp]
         lib.gsd_commit_kv.argtypes = [i32, i32, i32, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
+        lib.gsd_softmax_stats.argtypes = [i64, i32, ctypes.c_int, vp, i64, vp, vp, vp]
+        lib.gsd_accept_stochastic.argtypes = [ctypes.POINTER(StochasticDesc), vp]
         _lib = lib
     return _lib
 
@@ -345,3 +361,56 @@ def gsd_commit_kv(k, v, kv_offsets, prefix_lens, accept_len, accept_path, new_pr
                                         _ptr(accept_len), _ptr(accept_path), _ptr(new_prefix_lens),
                                         _stream_ptr(stream)))
     return new_prefix_lens
+
+
+def gsd_softmax_stats(logits, row_max=None, row_sumexp=None, stream=None):
+    """(row_max[r], row_sumexp[r]) of every logits row.  See gsd_softmax_stats in gsd.h."""
+    import torch
+    if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be a GPU tensor [rows, vocab] with a contiguous last dim")
+    rows, vocab = logits.shape
+    row_max = torch.empty(rows, dtype=torch.float32, device=logits.device) if row_max is None else row_max
+    row_sumexp = torch.empty(rows, dtype=torch.float32, device=logits.device) if row_sumexp is None else row_sumexp
+    _require(row_max, torch.float32, "row_max")
+    _require(row_sumexp, torch.float32, "row_sumexp")
+    _check(load_library().gsd_softmax_stats(rows, vocab, _dtype_code(logits), _ptr(logits), logits.stride(0),
+                                            _ptr(row_max), _ptr(row_sumexp), _stream_ptr(stream)))
+    return row_max, row_sumexp
+
+
+def gsd_accept_stochastic(node_offsets, parent_offsets, parent_idx, tokens, logits, root_logits, draft_logits,
+                          root_draft_logits, draft_prob, accept_u, resample_u, max_nodes: int, stream=None):
+    """Non-deterministic verification; returns (accept_len[B], accept_path[B, max_nodes], end_node[B], bonus_token[B],
+    row_max[T+B], row_sumexp[T+B]).  See gsd_accept_stochastic in gsd.h."""
+    import torch
+    for t, name in ((node_offsets, "node_offsets"), (parent_offsets, "parent_offsets"), (parent_idx, "parent_idx"),
+                    (tokens, "tokens")):
+        _require(t, torch.int32, name)
+    for t, name in ((draft_prob, "draft_prob"), (accept_u, "accept_u"), (resample_u, "resample_u")):
+        _require(t, torch.float32, name)
+    code = _dtype_code(logits)
+    T, V = logits.shape
+    B = node_offsets.numel() - 1
+    for t, name, rows in ((logits, "logits", T), (root_logits, "root_logits", B), (draft_logits, "draft_logits", T),
+                          (root_draft_logits, "root_draft_logits", B)):
+        if not t.is_cuda or t.dim() != 2 or t.shape != (rows, V) or t.stride(1) != 1 or _dtype_code(t) != code or \
+                (rows > 1 and t.stride(0) != logits.stride(0)):
+            raise ValueError(f"{name} must be a GPU tensor [{rows}, {V}] of the same dtype and row stride as logits")
+    dev = logits.device
+    d = StochasticDesc()
+    d.batch, d.total_nodes, d.max_nodes, d.vocab, d.dtype = B, T, int(max_nodes), V, code
+    d.row_stride = logits.stride(0)
+    out = {"row_max": torch.empty(T + B, dtype=torch.float32, device=dev),
+           "row_sumexp": torch.empty(T + B, dtype=torch.float32, device=dev),
+           "accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+           "accept_path": torch.empty((B, max_nodes), dtype=torch.int32, device=dev),
+           "end_node": torch.empty(B, dtype=torch.int32, device=dev),
+           "bonus_token": torch.empty(B, dtype=torch.int32, device=dev)}
+    for name, t in (("node_offsets", node_offsets), ("parent_offsets", parent_offsets), ("parent_idx", parent_idx),
+                    ("tokens", tokens), ("logits", logits), ("root_logits", root_logits),
+                    ("draft_logits", draft_logits), ("root_draft_logits", root_draft_logits),
+                    ("draft_prob", draft_prob), ("accept_u", accept_u), ("resample_u", resample_u), *out.items()):
+        setattr(d, name, t.data_ptr())
+    _check(load_library().gsd_accept_stochastic(ctypes.byref(d), _stream_ptr(stream)))
+    return (out["accept_len"], out["accept_path"], out["end_node"], out["bonus_token"], out["row_max"],
+            out["row_sumexp"])

@@ -1,0 +1,383 @@
+// Non-deterministic verification (paper Section 3: the i-th drafted token is accepted with probability
+// min(1, p/q), the first rejection discards the rest of the hypothesis and the LLM regenerates that token;
+// Section 6.4: the setting on token graphs).  Three kernels:
+//
+//   softmax_stats_kernel    one pass over a logits row: running (max, sum of exp(x - max)) per lane, merged across
+//                           the work-group: the normaliser of the LLM's distribution after every node.  HBM-bound,
+//                           same traffic as the argmax pass of deterministic verification.
+//   accept_stochastic_kernel one work-group per sequence: every edge r -> i is tested once,
+//                               accept_u[i] * draft_prob[i] < p_r(token_i)      (<=> u < min(1, p/q) for u < 1)
+//                           with p_r(token_i) = exp(logit - max_r) / sum_r gathered from the row of r, then the same
+//                           relaxation, end-node choice and back-walk as the deterministic kernel.
+//   resample_kernel         one work-group per sequence: the regenerated token, drawn by inverse CDF from
+//                           max(p - q, 0) at the end of the accepted path (from p if that node has no children or the
+//                           residual is empty).  Every thread owns a contiguous slice of the vocabulary, slice sums
+//                           are scanned in thread order, the owning thread walks its slice: one fixed summation order.
+#include "gsd_internal.h"
+
+namespace gsd {
+
+__device__ __forceinline__ float load_logit(const void *base, int64_t elem, int dtype) {
+    if (dtype == GSD_BF16) return __uint_as_float(uint32_t(reinterpret_cast<const uint16_t *>(base)[elem]) << 16);
+    return reinterpret_cast<const float *>(base)[elem];
+}
+
+// (m, s) <- merge of two partial softmax states: s counts exp(x - m)
+__device__ __forceinline__ void merge_state(float &m, float &s, float m2, float s2) {
+    const float mm = fmaxf(m, m2);
+    if (mm == -__builtin_inff()) {          // both empty (or all -inf so far)
+        m = mm;
+        s = 0.f;
+        return;
+    }
+    s = s * __expf(m - mm) + s2 * __expf(m2 - mm);
+    m = mm;
+}
+
+template <int THREADS, bool BF16>
+__global__ __launch_bounds__(THREADS) void softmax_stats_kernel(int32_t vocab, const void *__restrict__ logits,
+                                                                int64_t row_stride, float *__restrict__ row_max,
+                                                                float *__restrict__ row_sumexp) {
+    constexpr int ELT = BF16 ? 2 : 4;
+    constexpr int PER_VEC = 16 / ELT;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const int64_t row = blockIdx.x;
+    const char *row_ptr = reinterpret_cast<const char *>(logits) + row * row_stride * ELT;
+    float m = -__builtin_inff(), s = 0.f;
+    // a batch of values joins the running state with one rescale: max of the batch first, then its exponentials
+    auto add_batch = [&](const float *x, int cnt) {
+        float bm = -__builtin_inff();
+        for (int j = 0; j < cnt; ++j) bm = fmaxf(bm, x[j]);
+        if (bm == -__builtin_inff()) return;
+        const float mm = fmaxf(m, bm);
+        float add = 0.f;
+        for (int j = 0; j < cnt; ++j) add += __expf(x[j] - mm);
+        s = s * __expf(m - mm) + add;
+        m = mm;
+    };
+    // scalar head up to the first 16-byte boundary, 16-byte body, scalar tail
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(row_ptr);
+    int head = int(((16 - (addr & 15)) & 15) / ELT);
+    if (head > vocab) head = vocab;
+    const int nvec = (vocab - head) / PER_VEC;
+    const int tail_start = head + nvec * PER_VEC;
+    auto scalar_at = [&](int32_t i) -> float {
+        if (BF16) return __uint_as_float(uint32_t(reinterpret_cast<const uint16_t *>(row_ptr)[i]) << 16);
+        return reinterpret_cast<const float *>(row_ptr)[i];
+    };
+    if (int(threadIdx.x) < head) {
+        const float x = scalar_at(threadIdx.x);
+        add_batch(&x, 1);
+    }
+    const u32x4 *vec = reinterpret_cast<const u32x4 *>(row_ptr + size_t(head) * ELT);
+    for (int c = threadIdx.x; c < nvec; c += THREADS) {
+        const u32x4 w = __builtin_nontemporal_load(vec + c);
+        float x[PER_VEC];
+        if (BF16) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[2 * j] = __uint_as_float(w[j] << 16);
+                x[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(w[j]);
+        }
+        add_batch(x, PER_VEC);
+    }
+    {
+        const int i = tail_start + threadIdx.x;
+        if (i < vocab) {
+            const float x = scalar_at(i);
+            add_batch(&x, 1);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float m2 = __shfl_xor(m, off, 64), s2 = __shfl_xor(s, off, 64);
+        merge_state(m, s, m2, s2);
+    }
+    __shared__ float sm[THREADS / 64], ss[THREADS / 64];
+    if ((threadIdx.x & 63) == 0) {
+        sm[threadIdx.x >> 6] = m;
+        ss[threadIdx.x >> 6] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float M = sm[0], S = ss[0];
+        for (int w = 1; w < THREADS / 64; ++w) merge_state(M, S, sm[w], ss[w]);
+        row_max[row] = M;
+        row_sumexp[row] = S;
+    }
+}
+
+hipError_t launch_softmax_stats(int64_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
+                                float *row_max, float *row_sumexp, hipStream_t stream) {
+    if (dtype == GSD_BF16)
+        hipLaunchKernelGGL((softmax_stats_kernel<256, true>), dim3((unsigned)rows), dim3(256), 0, stream, vocab, logits,
+                           row_stride, row_max, row_sumexp);
+    else
+        hipLaunchKernelGGL((softmax_stats_kernel<256, false>), dim3((unsigned)rows), dim3(256), 0, stream, vocab, logits,
+                           row_stride, row_max, row_sumexp);
+    return hipGetLastError();
+}
+
+constexpr int kStochThreads = 512;
+constexpr int kStochEdgeCache = 6144;
+
+__global__ __launch_bounds__(kStochThreads) void accept_stochastic_kernel(const gsd_stochastic_desc d) {
+    __shared__ int32_t L[GSD_MAX_NODES_PER_SEQ];
+    __shared__ int32_t path_s[GSD_MAX_NODES_PER_SEQ];
+    __shared__ int32_t off_cache[GSD_MAX_NODES_PER_SEQ + 1];
+    __shared__ int32_t edge_cache[kStochEdgeCache];      // parent id, or INT32_MIN for a rejected / malformed edge
+    __shared__ uint32_t wave_best[kStochThreads / 64];
+    __shared__ int32_t len_s;
+
+    const int b = blockIdx.x;
+    const int64_t base = d.node_offsets[b];
+    int n = d.node_offsets[b + 1] - d.node_offsets[b];
+    if (n > d.max_nodes) n = d.max_nodes;
+    if (n < 0) n = 0;
+    const int32_t e0 = d.parent_offsets[base];
+    const int32_t e1 = d.parent_offsets[base + n];
+    const bool cached = (e1 - e0) <= kStochEdgeCache;    // larger graphs re-test their edges on every sweep
+    const float *root_max = d.row_max + d.total_nodes, *root_sum = d.row_sumexp + d.total_nodes;
+
+    // one edge: does the coin of child i pass against the LLM's probability of its token after parent r ?
+    auto edge_passes = [&](int i, int r) -> bool {
+        const int32_t tok = d.tokens[base + i];
+        if (tok < 0 || tok >= d.vocab) return false;     // a token outside the vocabulary is never accepted
+        float logit, mx, sm;
+        if (r == -1) {
+            logit = load_logit(d.root_logits, int64_t(b) * d.row_stride + tok, d.dtype);
+            mx = root_max[b];
+            sm = root_sum[b];
+        } else {
+            logit = load_logit(d.logits, (base + r) * d.row_stride + tok, d.dtype);
+            mx = d.row_max[base + r];
+            sm = d.row_sumexp[base + r];
+        }
+        const float prob = __expf(logit - mx) / sm;
+        return d.accept_u[base + i] * d.draft_prob[base + i] < prob;
+    };
+
+    for (int i = threadIdx.x; i <= n; i += kStochThreads) off_cache[i] = d.parent_offsets[base + i] - e0;
+    for (int i = threadIdx.x; i < n; i += kStochThreads) L[i] = -1;
+    __syncthreads();
+    if (cached) {
+        // edges are tested once, in parallel over edges: find the child of edge e by binary search over the offsets
+        for (int e = threadIdx.x; e < e1 - e0; e += kStochThreads) {
+            int lo = 0, hi = n;                  // off_cache[lo] <= e < off_cache[hi]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (off_cache[mid] <= e) lo = mid; else hi = mid;
+            }
+            const int i = lo;
+            const int r = d.parent_idx[e0 + e];
+            const bool ok = r >= -1 && r < i && edge_passes(i, r);
+            edge_cache[e] = ok ? r : INT32_MIN;
+        }
+    }
+    __syncthreads();
+
+    auto edge_parent = [&](int i, int e) -> int {        // accepted parent of edge e of node i, or INT32_MIN
+        if (cached) return edge_cache[e];
+        const int r = d.parent_idx[e0 + e];
+        return (r >= -1 && r < i && edge_passes(i, r)) ? r : INT32_MIN;
+    };
+
+    for (int sweep = 0; sweep <= n; ++sweep) {
+        int changed = 0;
+        for (int i = threadIdx.x; i < n; i += kStochThreads) {
+            int32_t best = L[i];
+            for (int e = off_cache[i]; e < off_cache[i + 1]; ++e) {
+                const int r = edge_parent(i, e);
+                if (r == INT32_MIN) continue;
+                const int32_t lr = (r == -1) ? 0 : L[r];
+                if (lr >= 0 && lr + 1 > best) best = lr + 1;
+            }
+            if (best != L[i]) {
+                L[i] = best;
+                changed = 1;
+            }
+        }
+        if (!__syncthreads_or(changed)) break;
+    }
+
+    uint32_t key = 0;                                    // largest L, then smallest id
+    for (int i = threadIdx.x; i < n; i += kStochThreads) {
+        const int32_t l = L[i];
+        if (l > 0) {
+            const uint32_t k = uint32_t(l) * 1024u + uint32_t(1023 - i);
+            key = k > key ? k : key;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t other = __shfl_xor(key, off, 64);
+        key = other > key ? other : key;
+    }
+    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = key;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t k = 0;
+        for (int w = 0; w < kStochThreads / 64; ++w) k = wave_best[w] > k ? wave_best[w] : k;
+        const int32_t len = int32_t(k / 1024u);
+        int32_t v = (len > 0) ? int32_t(1023u - (k % 1024u)) : -1;
+        len_s = len;
+        d.accept_len[b] = len;
+        d.end_node[b] = v;
+        for (int pos = len - 1; pos >= 0; --pos) {
+            path_s[pos] = v;
+            int32_t chosen = 0x7fffffff;
+            for (int e = off_cache[v]; e < off_cache[v + 1]; ++e) {
+                const int r = edge_parent(v, e);
+                if (r == INT32_MIN) continue;
+                const int32_t lr = (r == -1) ? 0 : L[r];
+                if (lr == pos && r < chosen) chosen = r;
+            }
+            if (chosen == 0x7fffffff || chosen < 0) break;
+            v = chosen;
+        }
+    }
+    __syncthreads();
+    const int32_t len = len_s;
+    int32_t *out = d.accept_path + int64_t(b) * d.max_nodes;
+    for (int x = threadIdx.x; x < d.max_nodes; x += kStochThreads) out[x] = (x < len) ? path_s[x] : -1;
+}
+
+constexpr int kResampleThreads = 1024;
+
+__global__ __launch_bounds__(kResampleThreads) void resample_kernel(const gsd_stochastic_desc d) {
+    __shared__ float red_m[kResampleThreads / 64], red_s[kResampleThreads / 64];
+    __shared__ float part[kResampleThreads];
+    __shared__ float stat[4];
+    __shared__ int has_child_s, pick_s;
+
+    const int b = blockIdx.x;
+    const int64_t base = d.node_offsets[b];
+    int n = d.node_offsets[b + 1] - d.node_offsets[b];
+    if (n > d.max_nodes) n = d.max_nodes;
+    if (n < 0) n = 0;
+    const int end = d.end_node[b];
+    const int V = d.vocab;
+
+    // does the end node (or the root) have children ?
+    if (threadIdx.x == 0) {
+        has_child_s = 0;
+        pick_s = -1;
+    }
+    __syncthreads();
+    const int32_t e0 = d.parent_offsets[base], e1 = d.parent_offsets[base + n];
+    int mine = 0;
+    for (int e = e0 + threadIdx.x; e < e1; e += kResampleThreads) mine |= (d.parent_idx[e] == end);
+    if (mine) has_child_s = 1;
+
+    const void *p_row = end < 0 ? d.root_logits : d.logits;
+    const void *q_row = end < 0 ? d.root_draft_logits : d.draft_logits;
+    const int64_t row_off = (end < 0 ? int64_t(b) : base + end) * d.row_stride;
+    const float p_max = end < 0 ? d.row_max[d.total_nodes + b] : d.row_max[base + end];
+    const float p_sum = end < 0 ? d.row_sumexp[d.total_nodes + b] : d.row_sumexp[base + end];
+
+    // the draft row's own (max, sum)
+    float m = -__builtin_inff(), s = 0.f;
+    for (int x = threadIdx.x; x < V; x += kResampleThreads) merge_state(m, s, load_logit(q_row, row_off + x, d.dtype), 1.f);
+    for (int off = 32; off > 0; off >>= 1) {
+        const float m2 = __shfl_xor(m, off, 64), s2 = __shfl_xor(s, off, 64);
+        merge_state(m, s, m2, s2);
+    }
+    if ((threadIdx.x & 63) == 0) {
+        red_m[threadIdx.x >> 6] = m;
+        red_s[threadIdx.x >> 6] = s;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float M = red_m[0], S = red_s[0];
+        for (int w = 1; w < kResampleThreads / 64; ++w) merge_state(M, S, red_m[w], red_s[w]);
+        stat[0] = M;
+        stat[1] = S;
+    }
+    __syncthreads();
+    const float q_max = stat[0], q_sum = stat[1];
+    const bool use_residual = has_child_s != 0;
+
+    // contiguous slice of the vocabulary per thread
+    const int per = (V + kResampleThreads - 1) / kResampleThreads;
+    const int x0 = threadIdx.x * per, x1 = min(V, x0 + per);
+    auto weight = [&](int x, bool residual) -> float {
+        const float p = __expf(load_logit(p_row, row_off + x, d.dtype) - p_max) / p_sum;
+        if (!residual) return p;
+        const float q = __expf(load_logit(q_row, row_off + x, d.dtype) - q_max) / q_sum;
+        return fmaxf(p - q, 0.f);
+    };
+    // total weight (thread-ordered scan in LDS, fixed order), falling back to p when the residual is empty
+    auto scan = [&](bool residual) -> float {
+        float local = 0.f;
+        for (int x = x0; x < x1; ++x) local += weight(x, residual);
+        __syncthreads();
+        part[threadIdx.x] = local;
+        __syncthreads();
+        for (int dd = 1; dd < kResampleThreads; dd <<= 1) {      // inclusive scan
+            const float add = threadIdx.x >= dd ? part[threadIdx.x - dd] : 0.f;
+            __syncthreads();
+            part[threadIdx.x] += add;
+            __syncthreads();
+        }
+        return part[kResampleThreads - 1];
+    };
+    bool residual = use_residual;
+    float total = scan(residual);
+    if (residual && !(total > 0.f)) {
+        residual = false;
+        total = scan(false);
+    }
+    const float target = d.resample_u[b] * total;
+    const float before = threadIdx.x > 0 ? part[threadIdx.x - 1] : 0.f;
+    const float upto = part[threadIdx.x];
+    // the owner of the target walks its slice; the smallest token whose cumulative weight exceeds the target
+    if (before <= target && target < upto) {
+        float run = before;
+        int pick = -1;
+        for (int x = x0; x < x1; ++x) {
+            run += weight(x, residual);
+            if (run > target) {
+                pick = x;
+                break;
+            }
+        }
+        if (pick < 0) {                                     // rounding inside the slice: its last token with weight
+            for (int x = x1 - 1; x >= x0; --x)
+                if (weight(x, residual) > 0.f) {
+                    pick = x;
+                    break;
+                }
+        }
+        pick_s = pick;
+    }
+    __syncthreads();
+    if (pick_s < 0 && threadIdx.x == 0) {                    // target == total by rounding: the last token with weight
+        int pick = 0;
+        for (int x = V - 1; x >= 0; --x)
+            if (weight(x, residual) > 0.f) {
+                pick = x;
+                break;
+            }
+        pick_s = pick;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) d.bonus_token[b] = pick_s;
+}
+
+hipError_t launch_accept_stochastic(const gsd_stochastic_desc &d, hipStream_t stream) {
+    hipError_t err = launch_softmax_stats(d.total_nodes, d.vocab, d.dtype, d.logits, d.row_stride, d.row_max,
+                                          d.row_sumexp, stream);
+    if (err != hipSuccess) return err;
+    err = launch_softmax_stats(d.batch, d.vocab, d.dtype, d.root_logits, d.row_stride, d.row_max + d.total_nodes,
+                               d.row_sumexp + d.total_nodes, stream);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(accept_stochastic_kernel, dim3(d.batch), dim3(kStochThreads), 0, stream, d);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(resample_kernel, dim3(d.batch), dim3(kResampleThreads), 0, stream, d);
+    return hipGetLastError();
+}
+
+}  // namespace gsd

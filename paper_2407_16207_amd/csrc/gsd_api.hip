@@ -229,4 +229,39 @@ int gsd_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers, int64_t 
     return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_commit_kv launch");
 }
 
+int gsd_softmax_stats(int64_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride, float *row_max,
+                      float *row_sumexp, void *hip_stream) {
+    if (rows < 1 || rows > INT32_MAX || vocab < 1) return fail(GSD_ERR_INVALID_ARG, "rows and vocab must be >= 1");
+    if (dtype != GSD_F32 && dtype != GSD_BF16) return fail(GSD_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (!logits || !row_max || !row_sumexp) return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    if (row_stride < vocab) return fail(GSD_ERR_INVALID_ARG, "row_stride %lld < vocab %d", (long long)row_stride, vocab);
+    const uintptr_t elt = dtype == GSD_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(logits) % elt != 0) return fail(GSD_ERR_INVALID_ARG, "logits misaligned");
+    hipError_t err = gsd::launch_softmax_stats(rows, vocab, dtype, logits, row_stride, row_max, row_sumexp,
+                                               (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_softmax_stats launch");
+}
+
+int gsd_accept_stochastic(const gsd_stochastic_desc *desc, void *hip_stream) {
+    if (!desc) return fail(GSD_ERR_INVALID_ARG, "descriptor is NULL");
+    const gsd_stochastic_desc &d = *desc;
+    if (d.batch < 1 || d.total_nodes < 1 || d.max_nodes < 1 || d.vocab < 1)
+        return fail(GSD_ERR_INVALID_ARG, "batch, total_nodes, max_nodes and vocab must be >= 1");
+    if (d.max_nodes > GSD_MAX_NODES_PER_SEQ)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", d.max_nodes, GSD_MAX_NODES_PER_SEQ);
+    if (d.dtype != GSD_F32 && d.dtype != GSD_BF16) return fail(GSD_ERR_UNSUPPORTED, "dtype %d", d.dtype);
+    if (d.row_stride < d.vocab)
+        return fail(GSD_ERR_INVALID_ARG, "row_stride %lld < vocab %d", (long long)d.row_stride, d.vocab);
+    if (!d.node_offsets || !d.parent_offsets || !d.parent_idx || !d.tokens || !d.logits || !d.root_logits ||
+        !d.draft_logits || !d.root_draft_logits || !d.draft_prob || !d.accept_u || !d.resample_u || !d.row_max ||
+        !d.row_sumexp || !d.accept_len || !d.accept_path || !d.end_node || !d.bonus_token)
+        return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    const uintptr_t elt = d.dtype == GSD_BF16 ? 2 : 4;
+    const void *rows4[4] = {d.logits, d.root_logits, d.draft_logits, d.root_draft_logits};
+    for (const void *ptr : rows4)
+        if (reinterpret_cast<uintptr_t>(ptr) % elt != 0) return fail(GSD_ERR_INVALID_ARG, "logits misaligned");
+    hipError_t err = gsd::launch_accept_stochastic(d, (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_accept_stochastic launch");
+}
+
 }  // extern "C"

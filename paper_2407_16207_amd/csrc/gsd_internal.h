@@ -41,4 +41,8 @@ hipError_t launch_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers
                             const int32_t *prefix_lens, const int32_t *accept_len, const int32_t *accept_path,
                             int32_t *new_prefix_lens, hipStream_t stream);
 
+hipError_t launch_softmax_stats(int64_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
+                                float *row_max, float *row_sumexp, hipStream_t stream);
+hipError_t launch_accept_stochastic(const gsd_stochastic_desc &d, hipStream_t stream);
+
 }  // namespace gsd

@@ -132,3 +132,28 @@ def test_unmerge_gather_commit_validate(lib):
         bad = list(good)
         bad[pos] = value
         assert lib.gsd_commit_kv(*bad) == code, pos
+
+
+def test_stochastic_entry_points_validate(lib):
+    p = ctypes.c_void_p(0x10000)
+    null = ctypes.c_void_p(0)
+    assert lib.gsd_softmax_stats(0, 10, 0, p, 10, p, p, null) == gsd.GSD_ERR_INVALID_ARG
+    assert lib.gsd_softmax_stats(4, 10, 0, p, 9, p, p, null) == gsd.GSD_ERR_INVALID_ARG
+    assert lib.gsd_softmax_stats(4, 10, 3, p, 10, p, p, null) == gsd.GSD_ERR_UNSUPPORTED
+    assert lib.gsd_softmax_stats(4, 10, 0, p, 10, null, p, null) == gsd.GSD_ERR_INVALID_ARG
+    assert lib.gsd_accept_stochastic(None, null) == gsd.GSD_ERR_INVALID_ARG
+
+    def good():
+        d = gsd.StochasticDesc()
+        d.batch, d.total_nodes, d.max_nodes, d.vocab, d.dtype, d.row_stride = 2, 64, 32, 1000, gsd.GSD_BF16, 1000
+        for name, _ in gsd.StochasticDesc._fields_:
+            if getattr(d, name) is None:
+                setattr(d, name, 0x10000)
+        return d
+    for field, value, code in (("batch", 0, gsd.GSD_ERR_INVALID_ARG), ("max_nodes", 1000, gsd.GSD_ERR_UNSUPPORTED),
+                               ("dtype", 9, gsd.GSD_ERR_UNSUPPORTED), ("row_stride", 999, gsd.GSD_ERR_INVALID_ARG),
+                               ("end_node", None, gsd.GSD_ERR_INVALID_ARG), ("draft_logits", None, gsd.GSD_ERR_INVALID_ARG),
+                               ("logits", 0x10001, gsd.GSD_ERR_INVALID_ARG)):
+        d = good()
+        setattr(d, field, value)
+        assert lib.gsd_accept_stochastic(ctypes.byref(d), null) == code, field

@@ -194,3 +194,128 @@ def test_tree_verification_end_to_end(gpu):
         tree_ids = rpath[b, :rl[b]]
         assert rto[o[b] + tree_ids].tolist() == dpath[b, :dl[b]].tolist()
     assert np.array_equal(dbonus, rbonus) and (rl > 0).any()
+
+
+# ---------------------------------------------------------------------------------- non-deterministic verify
+def stochastic_problem(rng, sizes, vocab, dtype, max_parents=3, peaked=2.0):
+    from paper_2407_16207_amd.workload import f32_to_bf16_bits
+    dags = [random_dag(rng, n, max_parents, 0.2) for n in sizes]
+    node_offsets, poff, pidx = pack(dags)
+    T, B = int(node_offsets[-1]), len(sizes)
+
+    def logits(rows):
+        x = (rng.standard_normal((rows, vocab)) * peaked).astype(np.float32)
+        return x if dtype == "f32" else f32_to_bf16_bits(x)
+    lp, lp_root, lq, lq_root = logits(T), logits(B), logits(T), logits(B)
+    p, _, _ = gsd_next.softmax_rows(lp)
+    p_root, _, _ = gsd_next.softmax_rows(lp_root)
+    q, _, _ = gsd_next.softmax_rows(lq)
+    q_root, _, _ = gsd_next.softmax_rows(lq_root)
+    # drafted tokens: mostly the draft model's likely ones, so that p/q is of order one
+    tokens = np.empty(T, dtype=np.int32)
+    draft_prob = np.empty(T, dtype=np.float32)
+    for b in range(B):
+        lo = int(node_offsets[b])
+        for i in range(sizes[b]):
+            e = int(poff[lo + i])
+            r = int(pidx[e]) if poff[lo + i + 1] > e else -1
+            qr = q_root[b] if r < 0 or r >= i else q[lo + r]
+            tok = int(rng.choice(vocab, p=qr))
+            tokens[lo + i] = tok
+            draft_prob[lo + i] = max(float(qr[tok]), 1e-6)
+    accept_u = rng.random(T).astype(np.float32)
+    resample_u = rng.random(B).astype(np.float32)
+    # keep every coin clear of its threshold (the GPU evaluates p in fp32): pull a close call well inside "accept"
+    for b in range(B):
+        lo = int(node_offsets[b])
+        for i in range(sizes[b]):
+            for e in range(int(poff[lo + i]), int(poff[lo + i + 1])):
+                r = int(pidx[e])
+                if r < -1 or r >= i:
+                    continue
+                pt = p_root[b, tokens[lo + i]] if r == -1 else p[lo + r, tokens[lo + i]]
+                thr = min(1.0, pt / draft_prob[lo + i])
+                if abs(accept_u[lo + i] - thr) < 1e-3 * max(thr, 1e-9) + 1e-7:
+                    accept_u[lo + i] = np.float32(0.5 * thr)
+    return dict(node_offsets=node_offsets, poff=poff, pidx=pidx, tokens=tokens, lp=lp, lp_root=lp_root, lq=lq,
+                lq_root=lq_root, p=p, p_root=p_root, q=q, q_root=q_root, draft_prob=draft_prob, accept_u=accept_u,
+                resample_u=resample_u, max_nodes=max(sizes))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_softmax_stats_and_stochastic_acceptance(gpu, dtype):
+    import paper_2407_16207_amd as gsd
+    rng = np.random.default_rng(31 if dtype == "f32" else 32)
+    pr = stochastic_problem(rng, [60, 1, 200, 17, 512, 33], 1003, dtype)
+    d = {k: gpu.to_dev(v) for k, v in pr.items() if isinstance(v, np.ndarray) and k not in ("p", "p_root", "q", "q_root")}
+    ln, path, end, bonus, row_max, row_sum = gsd.gsd_accept_stochastic(
+        d["node_offsets"], d["poff"], d["pidx"], d["tokens"], d["lp"], d["lp_root"], d["lq"], d["lq_root"],
+        d["draft_prob"], d["accept_u"], d["resample_u"], pr["max_nodes"])
+    torch.cuda.synchronize()
+    # normalisers against the fp64 softmax
+    _, m_ref, z_ref = gsd_next.softmax_rows(np.concatenate([pr["lp"], pr["lp_root"]]))
+    assert np.array_equal(row_max.cpu().numpy().astype(np.float64), m_ref)
+    assert np.abs(row_sum.cpu().numpy() / z_ref - 1).max() < 2e-6
+    m2, s2 = gsd.gsd_softmax_stats(d["lq"][:, 3:-2])            # misaligned rows, odd length
+    _, m_ref2, z_ref2 = gsd_next.softmax_rows(pr["lq"][:, 3:-2])
+    assert np.array_equal(m2.cpu().numpy().astype(np.float64), m_ref2) and np.abs(s2.cpu().numpy() / z_ref2 - 1).max() < 2e-6
+    # accepted paths: exact
+    rl, rpath, rbonus, _, cdfs = gsd_next.accept_stochastic(pr["node_offsets"], pr["poff"], pr["pidx"], pr["tokens"], pr["p"],
+                                                            pr["p_root"], pr["draft_prob"], pr["accept_u"], pr["q"],
+                                                            pr["q_root"], pr["resample_u"])
+    assert np.array_equal(ln.cpu().numpy(), rl) and np.array_equal(path.cpu().numpy(), rpath)
+    assert (rl > 0).sum() >= 3                   # the case is not trivial
+    ends = end.cpu().numpy()
+    for b in range(len(rl)):
+        assert ends[b] == (rpath[b, rl[b] - 1] if rl[b] else -1)
+    # regenerated token: the GPU sums in fp32 in its own order, so its draw is checked against the oracle's CDF: the
+    # target must fall into the drawn token's interval, up to the rounding of the partial sums
+    got = bonus.cpu().numpy()
+    exact = 0
+    for b, cdf in enumerate(cdfs):
+        x = int(got[b])
+        target = float(pr["resample_u"][b]) * cdf[-1]
+        lo_edge = cdf[x - 1] if x else 0.0
+        tol = 2e-5 * cdf[-1]
+        assert cdf[x] > lo_edge                      # a token that carries weight
+        assert lo_edge - tol <= target <= cdf[x] + tol, (b, x, rbonus[b])
+        exact += int(x == rbonus[b])
+    assert exact >= len(cdfs) - 1
+
+
+def test_stochastic_limits_on_gpu(gpu, ref):
+    """Coins at zero accept every edge with positive probability (the graph's deepest path); a one-hot LLM with a
+    certain draft reduces to deterministic verification."""
+    import paper_2407_16207_amd as gsd
+    rng = np.random.default_rng(77)
+    pr = stochastic_problem(rng, [90, 40], 257, "f32")
+    T, B, V = len(pr["tokens"]), 2, 257
+    d = {k: gpu.to_dev(v) for k, v in pr.items() if isinstance(v, np.ndarray) and k not in ("p", "p_root", "q", "q_root")}
+    zeros = torch.zeros(T, dtype=torch.float32, device="cuda")
+    ln, path, end, bonus, _, _ = gsd.gsd_accept_stochastic(d["node_offsets"], d["poff"], d["pidx"], d["tokens"], d["lp"],
+                                                          d["lp_root"], d["lq"], d["lq_root"], d["draft_prob"], zeros,
+                                                          d["resample_u"], pr["max_nodes"])
+    rl, rpath, _, _, _ = gsd_next.accept_stochastic(pr["node_offsets"], pr["poff"], pr["pidx"], pr["tokens"], pr["p"],
+                                                    pr["p_root"], pr["draft_prob"], np.zeros(T), pr["q"], pr["q_root"],
+                                                    pr["resample_u"])
+    assert np.array_equal(ln.cpu().numpy(), rl) and np.array_equal(path.cpu().numpy(), rpath) and (rl >= 3).all()
+    # one-hot LLM
+    pred = rng.integers(0, V, T + B)
+    lp = np.full((T + B, V), -80.0, dtype=np.float32)
+    lp[np.arange(T + B), pred] = 0.0
+    tokens = pr["tokens"].copy()
+    hit = rng.random(T) < 0.7                            # plant matches along first parents
+    for b in range(B):
+        lo = int(pr["node_offsets"][b])
+        for i in range(int(pr["node_offsets"][b + 1]) - lo):
+            r = int(pr["pidx"][pr["poff"][lo + i]])
+            if hit[lo + i]:
+                tokens[lo + i] = pred[T + b] if r < 0 else pred[lo + r]
+    ones = torch.ones(T, dtype=torch.float32, device="cuda")
+    u = torch.full((T,), 0.9, dtype=torch.float32, device="cuda")
+    ln, path, end, bonus, _, _ = gsd.gsd_accept_stochastic(d["node_offsets"], d["poff"], d["pidx"], gpu.to_dev(tokens),
+                                                          gpu.to_dev(lp[:T]), gpu.to_dev(lp[T:]), d["lq"], d["lq_root"], ones, u,
+                                                          d["resample_u"], pr["max_nodes"])
+    dl, dpath, dbonus = ref.accept_longest_path(pr["node_offsets"], pr["poff"], pr["pidx"], tokens, pred[:T].astype(np.int32),
+                                                pred[T:].astype(np.int32))
+    assert np.array_equal(ln.cpu().numpy(), dl) and np.array_equal(path.cpu().numpy(), dpath) and (dl > 0).any()
