@@ -174,3 +174,90 @@ def accept_stochastic(node_offsets, parent_offsets, parent_idx, tokens, p_nodes,
             x = int(np.flatnonzero(w > 0)[-1])
         bonus[b] = x
     return accept_len, accept_path, bonus, edge_ok, cdfs
+
+
+# -------------------------------------------------------------------------------------- graph construction
+def build_token_graph(node_offsets, tree_parent, tokens, draft_prob, tau, theta_prob, theta_sib):
+    """Draft-side construction of the token graph (Sections 4.2, 5.2, 5.3) from what the draft model would produce:
+    a token TREE per sequence (tree_parent[i] < i or -1, nodes in generation order = breadth first, so depths never
+    decrease along the ids), the drafted token of every node and the probability the draft model gave it.  Nodes are
+    visited in generation order:
+
+      * a node exists in the graph only if its parent is the root or an existing node that was expanded;
+      * probability pruning (Section 4.2): a node with draft_prob < theta_prob becomes a leaf;
+      * sibling pruning (Section 4.2): a node with draft_prob < theta_sib * (largest draft_prob among the children of
+        its parent, itself included) becomes a leaf;
+      * redundancy (Section 5.2): a node of depth >= tau whose tau-gram (its token and those of its tau-1 nearest
+        ancestors) equals the tau-gram of an EARLIER existing node is tau-redundant; the earliest such node is the
+        first occurrence F.  The redundant node R becomes a leaf (Section 5.3).  If F lies in the same layer as R its
+        children are still to be generated, and they are generated once for both: every child of F gets R as one
+        more parent (the merge edge).  If F lies in an earlier layer its children already exist above R; no edge is
+        drawn then (edges from a later layer back into an earlier one can close cycles, a case the paper does not
+        treat): R is a leaf all the same, which is where the saving comes from;
+      * a node is expanded iff none of the three made it a leaf.
+
+    Existing nodes keep their generation order (it is a topological order of the graph: every edge goes from one
+    layer to the next).  Returns packed arrays
+        (graph_node_offsets[B+1], parent_offsets[T'+1], parent_idx[E] (new sequence-local ids, ascending, -1 = root),
+         origin[T'] (tree id), flags[T'] bit0 = probability-pruned, bit1 = sibling-pruned, bit2 = redundant,
+         bit3 = redundant with its first occurrence in an earlier layer (no merge edge))."""
+    node_offsets = np.asarray(node_offsets, dtype=np.int64)
+    B = len(node_offsets) - 1
+    g_off, p_off, p_idx, origin_all, flags_all = [0], [0], [], [], []
+    for b in range(B):
+        lo, hi = int(node_offsets[b]), int(node_offsets[b + 1])
+        n = hi - lo
+        par = [int(x) for x in tree_parent[lo:hi]]
+        tok = [int(x) for x in tokens[lo:hi]]
+        q = [float(x) for x in draft_prob[lo:hi]]
+        exists = [False] * n
+        expanded = [False] * n
+        flags = [0] * n
+        depth = [0] * n
+        gram = [None] * n
+        merged_into = {}                          # F -> [R, ...] in generation order
+        # largest probability among the children of each parent (root = key -1): the children of a node exist all
+        # together or not at all, so this does not depend on what is kept
+        sib_max = {}
+        for i in range(n):
+            assert -1 <= par[i] < i
+            sib_max[par[i]] = max(sib_max.get(par[i], 0.0), q[i])
+            depth[i] = 1 if par[i] == -1 else depth[par[i]] + 1
+            assert i == 0 or depth[i] >= depth[i - 1], "nodes must come in breadth-first order"
+        for i in range(n):
+            p = par[i]
+            if not (p == -1 or (exists[p] and expanded[p])):
+                continue
+            exists[i] = True
+            if q[i] < theta_prob:
+                flags[i] |= 1
+            if q[i] < theta_sib * sib_max[p]:
+                flags[i] |= 2
+            if depth[i] >= tau:
+                g, v = [], i
+                for _ in range(tau):
+                    g.append(tok[v])
+                    v = par[v]
+                gram[i] = tuple(g)
+                for j in range(i):
+                    if exists[j] and gram[j] == gram[i]:
+                        flags[i] |= 4
+                        if depth[j] == depth[i]:
+                            merged_into.setdefault(j, []).append(i)
+                        else:
+                            flags[i] |= 8
+                        break
+            expanded[i] = flags[i] == 0
+        kept = [i for i in range(n) if exists[i]]
+        new_id = {old: k for k, old in enumerate(kept)}
+        for old in kept:
+            ps = [par[old]] + merged_into.get(par[old], [])
+            ps = [-1 if r == -1 else new_id[r] for r in ps]
+            assert ps == sorted(ps) and all(r < new_id[old] for r in ps)
+            p_idx.extend(ps)
+            p_off.append(len(p_idx))
+            origin_all.append(old)
+            flags_all.append(flags[old])
+        g_off.append(g_off[-1] + len(kept))
+    return (np.asarray(g_off, dtype=np.int32), np.asarray(p_off, dtype=np.int32), np.asarray(p_idx, dtype=np.int32),
+            np.asarray(origin_all, dtype=np.int32), np.asarray(flags_all, dtype=np.int32))

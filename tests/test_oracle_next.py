@@ -285,3 +285,152 @@ def test_first_emitted_token_is_distributed_as_the_llm_says():
                                                            rng.random(1), q[:1], q[1:], rng.random(1))
         counts[tok if ln[0] == 1 else bonus[0]] += 1
     assert np.abs(counts / trials - p[1]).max() < 4 * np.sqrt(0.25 / trials)     # four standard errors
+
+
+# -------------------------------------------------------------------------------------- graph construction
+def random_token_tree(rng, n, k, vocab):
+    """Breadth-first token tree: every node gets up to k children while ids last; tokens from a small vocabulary so
+    that n-grams do re-occur; draft probabilities decreasing among siblings."""
+    par, tok, q = [], [], []
+    frontier, nxt = [-1], []
+    while len(par) < n:
+        for p in frontier:
+            kids = int(rng.integers(1, k + 1))
+            probs = np.sort(rng.dirichlet(np.ones(kids + 1))[:kids])[::-1]
+            for c in range(kids):
+                if len(par) >= n:
+                    break
+                par.append(p); tok.append(int(rng.integers(0, vocab))); q.append(float(probs[c]))
+                nxt.append(len(par) - 1)
+        frontier, nxt = nxt, []
+        if not frontier:
+            break
+    return np.asarray(par, dtype=np.int32), np.asarray(tok, dtype=np.int32), np.asarray(q, dtype=np.float32)
+
+
+def graph_one(par, tok, q, tau, tp, ts):
+    n = len(par)
+    g_off, p_off, p_idx, origin, flags = gsd_next.build_token_graph([0, n], par, tok, q, tau, tp, ts)
+    assert g_off.tolist() == [0, len(origin)]
+    return p_off, p_idx, origin, flags
+
+
+def test_graph_without_pruning_or_merging_is_the_tree():
+    rng = np.random.default_rng(1)
+    par, tok, q = random_token_tree(rng, 60, 3, 50)
+    p_off, p_idx, origin, flags = graph_one(par, tok, q, 99, 0.0, 0.0)
+    assert origin.tolist() == list(range(60)) and p_idx.tolist() == par.tolist() and not flags.any()
+    assert p_off.tolist() == list(range(61))
+
+
+@pytest.mark.parametrize("seed", range(15))
+def test_pruning_keeps_exactly_the_nodes_below_unpruned_ancestors(seed):
+    rng = np.random.default_rng(50 + seed)
+    par, tok, q = random_token_tree(rng, 80, 3, 1000)
+    tp, ts = 0.15, 0.5
+    p_off, p_idx, origin, flags = graph_one(par, tok, q, 99, tp, ts)
+    sib_max = {}
+    for i, p in enumerate(par):
+        sib_max[int(p)] = max(sib_max.get(int(p), 0.0), float(q[i]))
+    leaf = [bool(q[i] < tp or q[i] < ts * sib_max[int(par[i])]) for i in range(len(par))]
+    want = []
+    for i in range(len(par)):
+        v, ok = int(par[i]), True
+        while v != -1:
+            ok &= not leaf[v]
+            v = int(par[v])
+        if ok:
+            want.append(i)
+    assert sorted(origin.tolist()) == want
+    for k, old in enumerate(origin):
+        assert bool(flags[k] & 1) == bool(q[old] < tp) and bool(flags[k] & 2) == bool(q[old] < ts * sib_max[int(par[old])])
+    # a tree stays a tree, parents keep their tokens' order
+    new_id = {int(o): k for k, o in enumerate(origin)}
+    assert all(p_idx[k] == (-1 if par[o] == -1 else new_id[int(par[o])]) for k, o in enumerate(origin))
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_merged_graph_spells_exactly_the_hypotheses_of_the_definition(seed):
+    """Independent statement of what merging means: a hypothesis continues below a redundant node with whatever
+    follows the first occurrence of its tau-gram.  The token sequences along the root paths of the built graph must be
+    exactly those, and among expanded nodes no tau-gram occurs twice."""
+    rng = np.random.default_rng(300 + seed)
+    tau = int(rng.integers(1, 4))
+    par, tok, q = random_token_tree(rng, int(rng.integers(5, 40)), 3, int(rng.integers(2, 6)))
+    n = len(par)
+    p_off, p_idx, origin, flags = graph_one(par, tok, q, tau, 0.0, 0.0)
+    m = len(origin)
+    # hypotheses spelled by the graph: un-merge it and read the tokens along every tree path
+    o, tpar, torg, cnt = gsd_next.unmerge_to_tree([0, m], p_off, p_idx, 200000)
+    assert cnt[0] < 200000
+    spelled = set()
+    for t in range(len(tpar)):
+        seq, v = [], t
+        while v != -1:
+            seq.append(int(tok[origin[torg[v]]]))
+            v = int(tpar[v])
+        spelled.add(tuple(reversed(seq)))
+    # the same from the definition, on the tree: replay the construction with plain sets
+    kids = {}
+    for i, p in enumerate(par):
+        kids.setdefault(int(p), []).append(i)
+    gram_of, first_seen, exists, follows = {}, {}, set(), {}
+    dep = [0] * n
+    for i in range(n):
+        dep[i] = 1 if par[i] == -1 else dep[int(par[i])] + 1
+    for i in range(n):
+        p = int(par[i])
+        if p != -1 and (p not in exists or follows[p] != p):
+            continue                                      # parent missing or a leaf
+        exists.add(i)
+        g, v = [], i
+        while v != -1 and len(g) < tau:
+            g.append(int(tok[v])); v = int(par[v])
+        follows[i] = i                                     # continues with its own children
+        if len(g) == tau:
+            key = tuple(g)
+            if key in first_seen:
+                f = first_seen[key]
+                follows[i] = f if dep[f] == dep[i] else None     # leaf; continues with f's children if f is in its layer
+            else:
+                first_seen[key] = i
+    want = set()
+
+    def walk(v, prefix):
+        prefix = prefix + (int(tok[v]),)
+        want.add(prefix)
+        src = follows[v]
+        if src is None:
+            return
+        for c in kids.get(src, []):
+            if c in exists:
+                walk(c, prefix)
+    for r in kids.get(-1, []):
+        walk(r, ())
+    assert spelled == want
+    grams = {}
+    for k, old in enumerate(origin):
+        if flags[k] == 0:
+            g, v = [], int(old)
+            while v != -1 and len(g) < tau:
+                g.append(int(tok[v])); v = int(par[v])
+            if len(g) == tau:
+                assert tuple(g) not in grams
+                grams[tuple(g)] = old
+    # numbering: parents first
+    for k in range(m):
+        assert all(r < k for r in p_idx[p_off[k]:p_off[k + 1]])
+
+
+def test_sibling_pruning_and_merge_hand_example():
+    # root -> 0 (A, .6), 1 (B, .3), 2 (C, .05);  0 -> 3 (X, .9);  1 -> 4 (X, .8);  3 -> 5 (Y, .7);  4 -> 6 (Y, .6)
+    par = np.array([-1, -1, -1, 0, 1, 3, 4], dtype=np.int32)
+    tok = np.array([10, 11, 12, 20, 20, 30, 30], dtype=np.int32)
+    q = np.array([.6, .3, .05, .9, .8, .7, .6], dtype=np.float32)
+    p_off, p_idx, origin, flags = graph_one(par, tok, q, 1, 0.1, 0.4)
+    # node 2: below theta_prob (0.05 < 0.1) and below 0.4 * 0.6 -> both pruning flags; node 1: 0.3 >= 0.24 stays
+    # tau = 1: node 4 repeats token X (first at 3) -> redundant leaf merged into 3; its child 6 is never generated;
+    # node 5 (child of 3) gets 4 as second parent and therefore moves behind it
+    assert origin.tolist() == [0, 1, 2, 3, 4, 5]
+    assert flags.tolist() == [0, 0, 3, 0, 4, 0]
+    assert p_off.tolist() == [0, 1, 2, 3, 4, 5, 7] and p_idx.tolist() == [-1, -1, -1, 0, 1, 3, 4]
