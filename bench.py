@@ -233,6 +233,49 @@ def bench_stochastic(gsd, w, dev, logits, stream, reps=20):
                     "(includes the binding's output allocations)"}
 
 
+def bench_build_graph(gsd, w, dev, stream, reps=20):
+    """Draft-side graph construction on synthetic token trees (breadth first, up to 4 children per node, tokens from
+    a small alphabet so that n-grams recur as they do in real drafts), with the paper's pilot-study thresholds."""
+    import numpy as np
+    import torch
+    cfg = w.cfg
+    rng = np.random.default_rng(w.seed + 4000)
+    n, k, vocab, tau = 512, 4, 40, 2
+    node_offsets, par, tok, q = [0], [], [], []
+    for _ in range(cfg.batch):
+        p_, t_, q_ = [], [], []
+        frontier = [-1]
+        while len(p_) < n and frontier:
+            nxt = []
+            for pnode in frontier:
+                kids = int(rng.integers(1, k + 1))
+                probs = np.sort(rng.dirichlet(np.ones(kids + 1))[:kids])[::-1]
+                for c in range(kids):
+                    if len(p_) >= n:
+                        break
+                    p_.append(pnode); t_.append(int(rng.integers(0, vocab))); q_.append(float(probs[c]))
+                    nxt.append(len(p_) - 1)
+            frontier = nxt
+        node_offsets.append(node_offsets[-1] + len(p_))
+        par += p_; tok += t_; q += q_
+    d_no = dev(np.asarray(node_offsets, dtype=np.int32))
+    d_par, d_tok, d_q = dev(np.asarray(par, dtype=np.int32)), dev(np.asarray(tok, dtype=np.int32)), dev(np.asarray(q, dtype=np.float32))
+    out = {}
+    for name, (tp, ts) in (("merge_only", (0.0, 0.0)), ("with_pruning", (0.2, 0.3))):
+        res = None
+
+        def call(i):
+            nonlocal res
+            res = gsd.gsd_build_token_graph(d_no, d_par, d_tok, d_q, n, tau, tp, ts)
+        ms = time_launches(stream, call, reps)
+        counts = res[5].cpu().numpy()
+        out[name] = {"theta_prob": tp, "theta_sib": ts, "graph_nodes": int(counts[:, 0].sum()),
+                     "graph_edges": int(counts[:, 1].sum()), "avg_call_ms": ms}
+    out["trees"] = f"{cfg.batch} token trees of {n} nodes, out-degree <= {k}, alphabet {vocab}, tau {tau}"
+    out["tree_nodes"] = int(node_offsets[-1])
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -451,6 +494,7 @@ def main():
                                               args.cache_layers)
         result["unmerge_to_tree"] = bench_unmerge(gsd, w, dev, stream)
         result["stochastic_verify"] = bench_stochastic(gsd, w, dev, logits, stream)
+        result["build_token_graph"] = bench_build_graph(gsd, w, dev, stream)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_nodes)
         result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]

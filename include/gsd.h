@@ -12,6 +12,7 @@
  *   gsd_unmerge_to_tree       token graph -> token tree with replicated successors (Section 5.4), gsd_gather_rows
  *   gsd_commit_kv             accepted path -> contiguous context rows of the KV cache (Section 6.5)
  *   gsd_accept_stochastic     non-deterministic verification (Sections 3, 6.4), gsd_softmax_stats
+ *   gsd_build_token_graph     drafted token tree -> pruned, merged token graph (Sections 4.2, 5.2, 5.3)
  *
  * Conventions common to all calls
  *   - Every data pointer is a DEVICE pointer owned by the caller; scalars and the descriptor struct are host
@@ -270,6 +271,37 @@ typedef struct gsd_stochastic_desc {
     int32_t *bonus_token;           /* [B] out */
 } gsd_stochastic_desc;
 int gsd_accept_stochastic(const gsd_stochastic_desc *desc, void *hip_stream);
+
+/*
+ * Draft-side construction of the token graph (Section 4.2: probability and sibling pruning; Section 5.2: tau-redundant
+ * nodes; Section 5.3: merging) from a drafted token TREE: per sequence, nodes in generation order (breadth first, so
+ * depths never decrease along the ids), tree_parent[i] < i or -1, the drafted token of every node and the probability
+ * the draft model gave it.  Visiting the nodes in that order:
+ *   - a node exists only if its parent is the root or an existing node that was expanded;
+ *   - it becomes a leaf if draft_prob < theta_prob, or if draft_prob < theta_sib * (largest draft_prob among its
+ *     parent's children), both compared in fp32;
+ *   - it is tau-redundant, and a leaf, if its depth is >= tau and its tau-gram (its token and those of its tau-1
+ *     nearest ancestors) equals that of an earlier existing node; the earliest such node F is the first occurrence.
+ *     If F is in the same layer, F's children (generated next) also get the redundant node as a parent: the merge
+ *     edge.  If F is in an earlier layer no edge is drawn (F's children exist already; edges back into earlier layers
+ *     could close cycles, a case the paper leaves open);
+ *   - a node is expanded iff it is no leaf.
+ * Existing nodes keep their order (a topological order of the result), so the output is a valid graph for every call
+ * in this header.
+ *
+ *   tau >= 1; counts [B][2] int32 out (nodes and edges of each sequence's graph)
+ *   graph_node_offsets [B+1], parent_offsets [T+1] (only the first T'+1 entries are written), parent_idx
+ *   [edge_capacity] (new sequence-local ids, ascending within a node, -1 = root), origin [T] (tree id of each graph
+ *   node), flags [T]: bit0 probability-pruned, bit1 sibling-pruned, bit2 redundant, bit3 redundant without merge edge
+ *   error_flag [1] or NULL: bit0 set on malformed input (a parent id >= its child or < -1, ids not breadth first, more
+ *   than max_nodes nodes; such nodes are dropped), bit1 if edge_capacity was too small (parent_idx is then incomplete).
+ *   Never cleared.  Two launches on `hip_stream`; read graph_node_offsets / parent_offsets back to size what follows.
+ */
+int gsd_build_token_graph(int32_t batch, int32_t max_nodes, int32_t tau, float theta_prob, float theta_sib,
+                          const int32_t *node_offsets, const int32_t *tree_parent, const int32_t *tokens,
+                          const float *draft_prob, int32_t *counts, int32_t *graph_node_offsets, int32_t *parent_offsets,
+                          int32_t *parent_idx, int64_t edge_capacity, int32_t *origin, int32_t *flags,
+                          int32_t *error_flag, void *hip_stream);
 
 #ifdef __cplusplus
 }

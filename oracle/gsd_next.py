@@ -229,9 +229,10 @@ def build_token_graph(node_offsets, tree_parent, tokens, draft_prob, tau, theta_
             if not (p == -1 or (exists[p] and expanded[p])):
                 continue
             exists[i] = True
-            if q[i] < theta_prob:
+            # both thresholds are evaluated in fp32, the precision the probabilities come in
+            if np.float32(q[i]) < np.float32(theta_prob):
                 flags[i] |= 1
-            if q[i] < theta_sib * sib_max[p]:
+            if np.float32(q[i]) < np.float32(theta_sib) * np.float32(sib_max[p]):
                 flags[i] |= 2
             if depth[i] >= tau:
                 g, v = [], i

@@ -3,7 +3,8 @@ Speculative Decoding.  Argument marshalling only: torch supplies device memory a
 the path runs in the library's HIP kernels.  There is no CPU fallback; a missing library raises.
 
     gsd_build_mask, gsd_dag_attention, gsd_node_argmax, gsd_accept_longest_path,
-    gsd_unmerge_to_tree, gsd_gather_rows, gsd_commit_kv, gsd_softmax_stats, gsd_accept_stochastic
+    gsd_unmerge_to_tree, gsd_gather_rows, gsd_commit_kv, gsd_softmax_stats, gsd_accept_stochastic,
+    gsd_build_token_graph
 
 mirror the C entry points of the same names.
 """
@@ -22,7 +23,8 @@ GSD_MAX_NODES_PER_SEQ = 512
 
 EXPORTS = ("gsd_status_string", "gsd_last_error", "gsd_version", "gsd_build_mask", "gsd_dag_attention_workspace",
            "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_node_argmax", "gsd_accept_longest_path",
-           "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv", "gsd_softmax_stats", "gsd_accept_stochastic")
+           "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv", "gsd_softmax_stats", "gsd_accept_stochastic",
+           "gsd_build_token_graph")
 
 
 class GsdError(RuntimeError):
@@ -103,6 +105,8 @@ def load_library() -> ctypes.CDLL:
         lib.gsd_commit_kv.argtypes = [i32, i32, i32, i64, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
         lib.gsd_softmax_stats.argtypes = [i64, i32, ctypes.c_int, vp, i64, vp, vp, vp]
         lib.gsd_accept_stochastic.argtypes = [ctypes.POINTER(StochasticDesc), vp]
+        lib.gsd_build_token_graph.argtypes = [i32, i32, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp,
+                                              vp, i64, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -414,3 +418,30 @@ def gsd_accept_stochastic(node_offsets, parent_offsets, parent_idx, tokens, logi
     _check(load_library().gsd_accept_stochastic(ctypes.byref(d), _stream_ptr(stream)))
     return (out["accept_len"], out["accept_path"], out["end_node"], out["bonus_token"], out["row_max"],
             out["row_sumexp"])
+
+
+def gsd_build_token_graph(node_offsets, tree_parent, tokens, draft_prob, max_nodes: int, tau: int, theta_prob: float,
+                          theta_sib: float, edge_capacity: int | None = None, error_flag=None, stream=None):
+    """Drafted token trees -> pruned, merged token graphs.  Returns (graph_node_offsets[B+1], parent_offsets[T+1],
+    parent_idx[edge_capacity], origin[T], flags[T], counts[B, 2]); only the first T' (+1) / E entries are written.
+    See gsd_build_token_graph in gsd.h."""
+    import torch
+    for t, name in ((node_offsets, "node_offsets"), (tree_parent, "tree_parent"), (tokens, "tokens")):
+        _require(t, torch.int32, name)
+    _require(draft_prob, torch.float32, "draft_prob")
+    B, T = node_offsets.numel() - 1, tokens.numel()
+    dev = tokens.device
+    cap = int(edge_capacity) if edge_capacity is not None else 8 * T
+    counts = torch.empty((B, 2), dtype=torch.int32, device=dev)
+    g_off = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    p_off = torch.empty(T + 1, dtype=torch.int32, device=dev)
+    p_idx = torch.empty(cap, dtype=torch.int32, device=dev)
+    origin = torch.empty(T, dtype=torch.int32, device=dev)
+    flags = torch.empty(T, dtype=torch.int32, device=dev)
+    if error_flag is not None:
+        _require(error_flag, torch.int32, "error_flag")
+    _check(load_library().gsd_build_token_graph(B, max_nodes, tau, theta_prob, theta_sib, _ptr(node_offsets),
+                                                _ptr(tree_parent), _ptr(tokens), _ptr(draft_prob), _ptr(counts),
+                                                _ptr(g_off), _ptr(p_off), _ptr(p_idx), cap, _ptr(origin), _ptr(flags),
+                                                _ptr(error_flag), _stream_ptr(stream)))
+    return g_off, p_off, p_idx, origin, flags, counts

@@ -264,4 +264,24 @@ int gsd_accept_stochastic(const gsd_stochastic_desc *desc, void *hip_stream) {
     return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_accept_stochastic launch");
 }
 
+int gsd_build_token_graph(int32_t batch, int32_t max_nodes, int32_t tau, float theta_prob, float theta_sib,
+                          const int32_t *node_offsets, const int32_t *tree_parent, const int32_t *tokens,
+                          const float *draft_prob, int32_t *counts, int32_t *graph_node_offsets, int32_t *parent_offsets,
+                          int32_t *parent_idx, int64_t edge_capacity, int32_t *origin, int32_t *flags,
+                          int32_t *error_flag, void *hip_stream) {
+    if (batch < 1 || max_nodes < 1 || tau < 1) return fail(GSD_ERR_INVALID_ARG, "batch, max_nodes and tau must be >= 1");
+    if (max_nodes > GSD_MAX_NODES_PER_SEQ)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", max_nodes, GSD_MAX_NODES_PER_SEQ);
+    if (!(theta_prob >= 0.f) || !(theta_sib >= 0.f)) return fail(GSD_ERR_INVALID_ARG, "thresholds must be >= 0");
+    if (edge_capacity < 1) return fail(GSD_ERR_INVALID_ARG, "edge_capacity must be >= 1");
+    if (!node_offsets || !tree_parent || !tokens || !draft_prob || !counts || !graph_node_offsets || !parent_offsets ||
+        !parent_idx || !origin || !flags)
+        return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    hipError_t err = gsd::launch_build_graph(batch, max_nodes, node_offsets, tree_parent, tokens, draft_prob, tau,
+                                             theta_prob, theta_sib, counts, graph_node_offsets, parent_offsets,
+                                             parent_idx, edge_capacity, origin, flags, error_flag,
+                                             (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_build_token_graph launch");
+}
+
 }  // extern "C"

@@ -45,4 +45,10 @@ hipError_t launch_softmax_stats(int64_t rows, int32_t vocab, int dtype, const vo
                                 float *row_max, float *row_sumexp, hipStream_t stream);
 hipError_t launch_accept_stochastic(const gsd_stochastic_desc &d, hipStream_t stream);
 
+hipError_t launch_build_graph(int32_t batch, int32_t max_nodes, const int32_t *node_offsets, const int32_t *tree_parent,
+                              const int32_t *tokens, const float *draft_prob, int32_t tau, float theta_prob,
+                              float theta_sib, int32_t *counts, int32_t *graph_node_offsets, int32_t *parent_offsets,
+                              int32_t *parent_idx, int64_t edge_capacity, int32_t *origin, int32_t *flags,
+                              int32_t *error_flag, hipStream_t stream);
+
 }  // namespace gsd
