@@ -52,24 +52,43 @@ __global__ __launch_bounds__(THREADS) void node_argmax_kernel(int32_t vocab, con
 
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     const u32x4 *vec = reinterpret_cast<const u32x4 *>(row_ptr + size_t(head) * ELT);
+    // Body: a lane only tracks the largest value and the 16-byte chunk it came from (one max tree and one compare
+    // per chunk instead of a compare-and-select per element; the loads, not the ALU, should set the pace), and
+    // looks the element up in that chunk afterwards.  Chunks come in ascending order, so a strict > keeps the
+    // first chunk that holds the lane's maximum; NaN loses every v_max and every compare.
+    float body_max = -__builtin_inff();
+    int body_chunk = -1;
+    auto chunk_values = [&](const u32x4 w, float (&x)[PER_VEC]) {
+        if (BF16) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                x[2 * j] = bf16_lo(w[j]);
+                x[2 * j + 1] = bf16_hi(w[j]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(w[j]);
+        }
+    };
     for (int c = threadIdx.x; c < nvec; c += THREADS) {
         const u32x4 w = __builtin_nontemporal_load(vec + c);
-        const int32_t i0 = head + c * PER_VEC;
-        if (BF16) {
-            consider(best, bf16_lo(w.x), i0 + 0);
-            consider(best, bf16_hi(w.x), i0 + 1);
-            consider(best, bf16_lo(w.y), i0 + 2);
-            consider(best, bf16_hi(w.y), i0 + 3);
-            consider(best, bf16_lo(w.z), i0 + 4);
-            consider(best, bf16_hi(w.z), i0 + 5);
-            consider(best, bf16_lo(w.w), i0 + 6);
-            consider(best, bf16_hi(w.w), i0 + 7);
-        } else {
-            consider(best, __uint_as_float(w.x), i0 + 0);
-            consider(best, __uint_as_float(w.y), i0 + 1);
-            consider(best, __uint_as_float(w.z), i0 + 2);
-            consider(best, __uint_as_float(w.w), i0 + 3);
+        float x[PER_VEC];
+        chunk_values(w, x);
+        float m = x[0];
+#pragma unroll
+        for (int j = 1; j < PER_VEC; ++j) m = fmaxf(m, x[j]);
+        // the first chunk with any non-NaN value is taken even if that value is -inf (lowest index of an all -inf row)
+        if (m > body_max || (body_chunk < 0 && m == body_max)) {
+            body_max = m;
+            body_chunk = c;
         }
+    }
+    if (body_chunk >= 0) {
+        float x[PER_VEC];
+        chunk_values(vec[body_chunk], x);
+#pragma unroll
+        for (int j = PER_VEC - 1; j >= 0; --j)
+            if (x[j] == body_max) consider(best, x[j], head + body_chunk * PER_VEC + j);
     }
     {
         const int i = tail_start + threadIdx.x;
