@@ -197,6 +197,37 @@ def bench_unmerge(gsd, w, dev, stream, reps=20):
             "attention_cost_ratio_tree_over_graph": {"flops": tree_flops / dag_flops, "time": tree_ms / dag_ms}}
 
 
+def bench_matrix_pipe(gsd, w, q, k, v, kv_offsets, prefix_lens, node_offsets, mask, out, workspace, need, flops,
+                      stream, splits, reps=20):
+    """What the chip's matrix pipe sustains for these operand statistics, next to the attention kernel: a bare loop
+    of the same matrix instruction (two waves per SIMD on every CU, nothing else in it) fed with zeros and with
+    N(0,1) bf16 operands, and the attention launch itself on all-zero Q, K, V (same instruction stream, same
+    algorithmic flops).  The sustained clock of the matrix pipe depends on how much the operand bits toggle."""
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    wgs, iters = 4 * cus, 4000
+    g = torch.Generator(device="cuda")
+    g.manual_seed(w.seed + 29)
+    sink = torch.empty(wgs * 512, dtype=torch.float32, device="cuda")
+    loop_flops = wgs * 8.0 * iters * 16 * 32768
+    res = {}
+    for name, operands in (("zeros", torch.zeros(wgs * 512 * 16 * 8, dtype=torch.bfloat16, device="cuda")),
+                           ("normal", torch.randn(wgs * 512 * 16 * 8, generator=g, device="cuda",
+                                                  dtype=torch.float32).to(torch.bfloat16))):
+        ms = time_launches(stream, lambda i: gsd.gsd_diag_mfma_loop(operands, wgs, iters, sink=sink), 6, warmup=3)
+        res["bare_mfma_loop_tflops_" + name] = loop_flops / ms / 1e9
+    qz, kz, vz = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+    dz = gsd.make_attn_desc(qz, kz, vz, kv_offsets, prefix_lens, node_offsets, mask, w.max_nodes,
+                            int(w.prefix_lens.max()), w.softmax_scale, out=out, num_splits=splits)
+    dz.workspace, dz.workspace_bytes = workspace.data_ptr(), need
+    ms = time_launches(stream, lambda i: gsd.gsd_dag_attention_desc(dz), reps)
+    res["attention_ms_zero_inputs"] = ms
+    res["attention_tflops_zero_inputs"] = flops / ms / 1e9
+    res["note"] = ("same kernels, different operand bits: the rate with N(0,1) operands is bounded by the clock the chip "
+                   "sustains under that switching activity, not by the instruction schedule")
+    return res
+
+
 def bench_stochastic(gsd, w, dev, logits, stream, reps=20):
     """Non-deterministic verification on the step's graphs: the LLM's logits are the workload's, the draft model's
     logits are a second seeded draw of the same shape; reports the vocabulary-wide normaliser pass against HBM."""
@@ -495,6 +526,10 @@ def main():
         result["unmerge_to_tree"] = bench_unmerge(gsd, w, dev, stream)
         result["stochastic_verify"] = bench_stochastic(gsd, w, dev, logits, stream)
         result["build_token_graph"] = bench_build_graph(gsd, w, dev, stream)
+        result["matrix_pipe_sustained"] = bench_matrix_pipe(gsd, w, q, k, v, kv_offsets, prefix_lens, node_offsets,
+                                                            mask, out, workspace, need, flops, stream, args.splits)
+        result["roofline"]["achieved_over_bare_mfma_loop_same_operand_statistics"] = (
+            attn_tflops / result["matrix_pipe_sustained"]["bare_mfma_loop_tflops_normal"])
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_nodes)
         result["cpu_baseline"]["gpu_over_cpu"] = result["value"] / result["cpu_baseline"]["value"]

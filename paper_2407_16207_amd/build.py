@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libgsd.so")
 
 SOURCES = ["gsd_api.hip", "mask_build.hip", "accept_path.hip", "node_argmax.hip", "dag_attention_f32.hip",
-           "dag_attention_bf16.hip", "unmerge_tree.hip", "commit_kv.hip", "accept_stochastic.hip", "build_graph.hip"]
+           "dag_attention_bf16.hip", "unmerge_tree.hip", "commit_kv.hip", "accept_stochastic.hip", "build_graph.hip", "diag_mfma.hip"]
 
 # -no-hip-rt: the library carries no dependency on a particular libamdhip64; the process that loads it (the
 # Python binding: the runtime torch already runs on) supplies the HIP runtime.  Two HIP runtimes in one process

@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "gsd_internal.h"
+#include "gsd_diag.h"
 
 namespace {
 
@@ -282,6 +283,19 @@ int gsd_build_token_graph(int32_t batch, int32_t max_nodes, int32_t tau, float t
                                              parent_idx, edge_capacity, origin, flags, error_flag,
                                              (hipStream_t)hip_stream);
     return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_build_token_graph launch");
+}
+
+int gsd_diag_mfma_loop(const void *operands, int64_t operand_bytes, int32_t work_groups, int32_t iters, float *sink,
+                       void *hip_stream) {
+    if (!operands || !sink) return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    if (operand_bytes < 16 || operand_bytes % 16 != 0 || operand_bytes / 16 > INT64_C(0xffffffff))
+        return fail(GSD_ERR_INVALID_ARG, "operand_bytes %lld must be a positive multiple of 16", (long long)operand_bytes);
+    if (reinterpret_cast<uintptr_t>(operands) % 16 != 0) return fail(GSD_ERR_INVALID_ARG, "operands misaligned");
+    if (work_groups < 1 || work_groups > 65536 || iters < 1 || iters > (1 << 20))
+        return fail(GSD_ERR_INVALID_ARG, "work_groups %d or iters %d out of range", work_groups, iters);
+    hipError_t err = gsd::launch_diag_mfma_loop(operands, operand_bytes, work_groups, iters, sink,
+                                                (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_diag_mfma_loop launch");
 }
 
 }  // extern "C"

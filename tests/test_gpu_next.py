@@ -386,3 +386,15 @@ def test_build_token_graph_flags_bad_input_and_small_capacity(gpu):
                                     0.0, 0.0, edge_capacity=3, error_flag=flag)
     torch.cuda.synchronize()
     assert flag.item() & 2
+
+
+def test_measurement_aid_counts_what_it_says(gpu):
+    """The bare matrix-instruction loop really issues iters*16 instructions per lane: with all-ones operands every
+    instruction adds 16 to each of a lane's 64 accumulator elements, four instructions per accumulator block and trip."""
+    import paper_2407_16207_amd as gsd
+    ones = torch.ones(4096, dtype=torch.bfloat16, device="cuda")
+    for wgs, iters in ((3, 1), (5, 7)):
+        sink = gsd.gsd_diag_mfma_loop(ones, wgs, iters)
+        torch.cuda.synchronize()
+        assert sink.numel() == wgs * 512
+        assert torch.all(sink == 64.0 * 16.0 * 4 * iters)
