@@ -151,6 +151,10 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     constexpr int NQK = 2 * KS;         // matrix instructions of S^T = K Q^T per tile
     constexpr int NPV = 4 * MBD;        // matrix instructions of O^T += V^T P^T per tile
     constexpr int CHUNKS = D / 8;       // 16-byte chunks per K/V row
+    // Of a lane's 32 scores per tile, the first B_SCORES are converted in phase B, the rest in phase A.  Measured
+    // at 4, 8, 12 and 16: within half a percent of each other.
+    constexpr int B_SCORES = 16;
+    static_assert(B_SCORES % 2 == 0 && B_SCORES >= 2 && B_SCORES <= 16, "");
     using L = Lds<D>;
     constexpr int RB = L::kRowBytes;
     constexpr int RPI = 1024 / RB;      // tile rows moved by one wave-wide 16-byte-per-lane copy
@@ -509,8 +513,8 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     };
 
     // The exponentials are the vector ALU's heaviest load, so they are split between the two phases: phase B of
-    // step i-1 converts scores 0..15 of tile i (right after it has found the tile's max), phase A of step i
-    // converts scores 16..31.  A slice is one K or V fragment's worth of matrix instructions (one per row block).
+    // step i-1 converts scores 0..B_SCORES-1 of tile i (right after it has found the tile's max), phase A of step i
+    // converts the rest.  A slice is one K or V fragment's worth of matrix instructions (one per row block).
     //
     // phase A.  HAS_NEXT: also compute the raw scores of the next tile from K buffer `kbuf` into s_next, and spread
     // the copy of the next tile's V (tile `v_tile` into V buffer `v_buf`) over the slices: issued back to back after
@@ -518,7 +522,7 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     auto phase_a = [&](auto has_next_tag, auto full_tag, int kbuf, floatx16 (&sc)[RBW][2], floatx16 (&s_next)[RBW][2], int v_tile, int v_buf, int v_cur) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;     // the tile being copied is a full prefix tile
-        constexpr int PAIRS = 8 * RBW;              // pairs of scores converted here; pair q goes into slice q*NQK/PAIRS
+        constexpr int PAIRS = (32 - B_SCORES) / 2 * RBW;   // pairs of scores converted here; pair q goes into slice q*NQK/PAIRS
         float sum[RBW];
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) sum[rb] = 0.f;
@@ -533,27 +537,34 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         GSD_SLICE_END();
 #pragma unroll
         for (int idx = 0; idx < NQK; ++idx) {
-            if (HAS_NEXT) {
+            // One sub-slice per row block: its matrix instruction, then the vector work of that row block.  A wave
+            // that issues two matrix instructions back to back sits blocked on the second until the pipe is free;
+            // with its share of the vector work in between it arrives there about when the pipe does.
 #pragma unroll
-                for (int rb = 0; rb < RBW; ++rb)
+            for (int rb = 0; rb < RBW; ++rb) {
+                if (HAS_NEXT) {
                     score_mfma(s_next[rb][idx & 1], kf[idx], rb, idx);
-                if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
-                else vpre[idx + 4 - NQK] = v_frag(v_cur, idx + 4 - NQK);   // phase B's first reads, ahead of the barrier
-                if (idx % (NQK / IPW) == 1) {
-                    if (FULL) dma_v_one_full(v_buf, idx / (NQK / IPW));
-                    else dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
+                    if (rb == RBW - 1) {
+                        if (idx + 4 < NQK) kf[idx + 4] = k_frag(kbuf, idx + 4);
+                        else vpre[idx + 4 - NQK] = v_frag(v_cur, idx + 4 - NQK);   // phase B's first reads, ahead of the barrier
+                        if (idx % (NQK / IPW) == 1) {
+                            if (FULL) dma_v_one_full(v_buf, idx / (NQK / IPW));
+                            else dma_v_one(v_tile, v_buf, idx / (NQK / IPW));
+                        }
+                    }
                 }
-            }
 #pragma unroll
-            for (int q = 0; q < PAIRS; ++q)
-                if ((q * NQK) / PAIRS == idx) convert_pair(sc[q % RBW], 16 + 2 * (q / RBW), sum[q % RBW], q % RBW);
-            GSD_SLICE_END();
+                for (int q = 0; q < PAIRS; ++q)
+                    if ((q * NQK) / PAIRS == idx && q % RBW == rb)
+                        convert_pair(sc[rb], B_SCORES + 2 * (q / RBW), sum[rb], rb);
+                GSD_SLICE_END();
+            }
         }
         // keep the conversions in this phase: without a use here the compiler sinks them next to their first use in
         // phase B, behind the barrier, and the overlap with the matrix pipe is lost
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
-            asm volatile("" : "+v"(pf[rb][2]), "+v"(pf[rb][3]), "+v"(sum[rb]));
+            asm volatile("" : "+v"(pf[rb][1]), "+v"(pf[rb][2]), "+v"(pf[rb][3]), "+v"(sum[rb]));
             if (HAS_NEXT) asm volatile("" : "+v"(s_next[rb][0]), "+v"(s_next[rb][1]));
             l_run[rb] += sum[rb];
         }
@@ -570,9 +581,9 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         constexpr int MAX_SLICES = NPV / 4;             // slices that reduce the max
         constexpr int MAX_PER_SLICE = 16 / MAX_SLICES;  // max3 operations (pairs of scores) per row block in each of them
         constexpr int CONV_FIRST = MAX_SLICES + 2;      // first slice that converts (decision and fix-up come before)
-        constexpr int PAIRS = 8 * RBW;                  // pair q goes into slice CONV_FIRST + q*(NPV - CONV_FIRST)/PAIRS
+        constexpr int PAIRS = B_SCORES / 2 * RBW;       // pair q goes into slice CONV_FIRST + q*(NPV - CONV_FIRST)/PAIRS
         // pf[.][0] is last read by slice MBD-1 and pf[.][1] by slice 2*MBD-1; they may be rewritten only after that
-        static_assert(CONV_FIRST >= MBD && CONV_FIRST + ((PAIRS / 2) * (NPV - CONV_FIRST)) / PAIRS >= 2 * MBD,
+        static_assert(CONV_FIRST >= MBD && (B_SCORES <= 8 || CONV_FIRST + ((4 * RBW) * (NPV - CONV_FIRST)) / PAIRS >= 2 * MBD),
                       "probabilities of the current tile would be overwritten before they are used");
         bf16x8 vf[NPV];
 #pragma unroll
@@ -594,40 +605,35 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         for (int idx = 0; idx < NPV; ++idx) {
             const int ks2 = idx / MBD, mbd = idx % MBD;
 #pragma unroll
-            for (int rb = 0; rb < RBW; ++rb)
+            for (int rb = 0; rb < RBW; ++rb) {      // sub-slices as in phase A
                 if (ASM_MFMA) mfma_a_acc(acc_o[rb][mbd], vf[idx], __builtin_bit_cast(bf16x8, pf[rb][ks2]));
                 else acc_o[rb][mbd] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[idx], __builtin_bit_cast(bf16x8, pf[rb][ks2]), acc_o[rb][mbd], 0, 0, 0);
-            if (idx + 4 < NPV) vf[idx + 4] = v_frag(vbuf, idx + 4);
-            else if (HAS_NEXT && k_ahead) kpre[idx + 4 - NPV] = k_frag(k_next_buf, idx + 4 - NPV);   // next phase A's first reads
-            if (COPY_K && idx % (NPV / IPW) == 1) {
-                if (FULL) dma_k_one_full(k_buf, idx / (NPV / IPW));
-                else dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
-            }
-            if (HAS_NEXT) {
-                if (idx < MAX_SLICES) {
-#pragma unroll
-                    for (int rb = 0; rb < RBW; ++rb)
+                if (rb == RBW - 1) {
+                    if (idx + 4 < NPV) vf[idx + 4] = v_frag(vbuf, idx + 4);
+                    else if (HAS_NEXT && k_ahead) kpre[idx + 4 - NPV] = k_frag(k_next_buf, idx + 4 - NPV);   // next phase A's first reads
+                    if (COPY_K && idx % (NPV / IPW) == 1) {
+                        if (FULL) dma_k_one_full(k_buf, idx / (NPV / IPW));
+                        else dma_k_one(k_tile, k_buf, idx / (NPV / IPW));
+                    }
+                }
+                if (HAS_NEXT) {
+                    if (idx < MAX_SLICES) {
 #pragma unroll
                         for (int x = 0; x < MAX_PER_SLICE; ++x) {
                             const int e = 2 * (idx * MAX_PER_SLICE + x);
                             if (x & 1) mx1[rb] = max3(mx1[rb], s_next[rb][e / 16][e % 16], s_next[rb][(e + 1) / 16][(e + 1) % 16]);
                             else mx0[rb] = max3(mx0[rb], s_next[rb][e / 16][e % 16], s_next[rb][(e + 1) / 16][(e + 1) % 16]);
                         }
-                }
-                if (idx == MAX_SLICES) {
+                    }
+                    if (idx == MAX_SLICES) decide_max(fmaxf(mx0[rb], mx1[rb]), rb);
+                    if (idx == MAX_SLICES + 1) apply_max(s_next[rb], rb);
 #pragma unroll
-                    for (int rb = 0; rb < RBW; ++rb) decide_max(fmaxf(mx0[rb], mx1[rb]), rb);
+                    for (int q = 0; q < PAIRS; ++q)
+                        if (CONV_FIRST + (q * (NPV - CONV_FIRST)) / PAIRS == idx && q % RBW == rb)
+                            convert_pair(s_next[rb], 2 * (q / RBW), sum[rb], rb);
                 }
-                if (idx == MAX_SLICES + 1) {
-#pragma unroll
-                    for (int rb = 0; rb < RBW; ++rb) apply_max(s_next[rb], rb);
-                }
-#pragma unroll
-                for (int q = 0; q < PAIRS; ++q)
-                    if (CONV_FIRST + (q * (NPV - CONV_FIRST)) / PAIRS == idx)
-                        convert_pair(s_next[q % RBW], 2 * (q / RBW), sum[q % RBW], q % RBW);
+                GSD_SLICE_END();
             }
-            GSD_SLICE_END();
         }
         if (HAS_NEXT) {
 #pragma unroll
@@ -671,7 +677,7 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
             apply_max(sa[rb], rb);
             float sum = 0.f;
 #pragma unroll
-            for (int e = 0; e < 16; e += 2) convert_pair(sa[rb], e, sum, rb);
+            for (int e = 0; e < B_SCORES; e += 2) convert_pair(sa[rb], e, sum, rb);
             l_run[rb] += sum;
         }
         wg_barrier();          // K buffer 0 has been read by every wave
