@@ -63,8 +63,7 @@ struct AttnParams {
     int32_t batch, total_nodes, max_nodes, num_q_heads, num_kv_heads, group, words_per_row;
     int32_t q_tiles;    // row tiles per (sequence, KV head)
     int32_t splits;
-    int32_t total_wg;   // q_tiles * splits * batch * num_kv_heads
-    int32_t wg_per_xcd; // ceil(total_wg / 8)
+    int32_t wg_per_xcd; // ceil(batch * num_kv_heads / 8) * q_tiles * splits
     float scale_log2e;  // softmax_scale * log2(e)
     float scale;
 };
@@ -166,20 +165,22 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     // buffer x of K at lds + x*kTileBytes, buffer x of V at lds + (2+x)*kTileBytes
 
     // ---- which piece of work: XCD-aware decode of the linear work-group id --------------------------------
-    // Hardware deals consecutive work-group ids round-robin to the 8 XCDs; give every XCD a contiguous range
-    // of logical ids so that the row tiles sharing one K/V stream run on one XCD and share its L2.
+    // Hardware deals consecutive work-group ids round-robin to the 8 XCDs.  A (sequence, KV head) group stays on
+    // one XCD, in consecutive slots, so that its row tiles run together and share the K/V stream in that XCD's L2;
+    // the groups themselves are dealt round-robin (group g on XCD g % 8), so that the KV heads of one sequence,
+    // which all have that sequence's length, are spread over the XCDs and ragged batches load them evenly.
     const int hw = blockIdx.x;
-    const int logical = (hw & 7) * p.wg_per_xcd + (hw >> 3);
-    if (logical >= p.total_wg) return;
-    const int qt = logical % p.q_tiles;
-    const int rest = logical / p.q_tiles;
-    const int split = rest % p.splits;
-    const int group_id = rest / p.splits;          // b * Hkv + kvh
-    const int b = group_id / p.num_kv_heads;
-    const int kvh = group_id - b * p.num_kv_heads;
-
+    const int per_group = p.q_tiles * p.splits;
+    const int xcd_slot = hw >> 3;
+    const int group_id = (xcd_slot / per_group) * 8 + (hw & 7);      // b * Hkv + kvh
+    if (group_id >= p.batch * p.num_kv_heads) return;
+    const int within = xcd_slot % per_group;
+    const int qt = within % p.q_tiles;
+    const int split = within / p.q_tiles;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
+    const int b = group_id / p.num_kv_heads;
+    const int kvh = group_id - b * p.num_kv_heads;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5;        // which 8-wide k group / which 4-row group of the accumulator
     const int col = lane & 31;         // query row inside the wave's 32
@@ -871,8 +872,7 @@ hipError_t launch_attention_bf16(const gsd_attn_desc &d, int splits, hipStream_t
     p.num_kv_heads = d.num_kv_heads; p.group = d.num_q_heads / d.num_kv_heads; p.words_per_row = d.words_per_row;
     p.q_tiles = q_tiles_of(d);
     p.splits = splits;
-    p.total_wg = p.q_tiles * splits * d.batch * d.num_kv_heads;
-    p.wg_per_xcd = (p.total_wg + 7) / 8;
+    p.wg_per_xcd = (d.batch * d.num_kv_heads + 7) / 8 * p.q_tiles * splits;
     p.scale = d.softmax_scale;
     p.scale_log2e = d.softmax_scale * kLog2e;
 
