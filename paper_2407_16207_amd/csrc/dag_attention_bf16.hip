@@ -842,11 +842,27 @@ int attention_bf16_splits(const gsd_attn_desc &d) {
     const int nt_max = (d.max_prefix + kKeysPerTile - 1) / kKeysPerTile + (d.max_nodes + kKeysPerTile - 1) / kKeysPerTile;
     int splits = d.num_splits;
     if (splits <= 0) {
-        // aim for sixteen wavefronts per compute unit in total; never fewer than 4 KV tiles per split
-        const int64_t base = int64_t(q_tiles_of(d)) * d.batch * d.num_kv_heads * waves_of(d);
-        splits = int((4096 + base - 1) / base);
-        const int cap = nt_max / 4 > 0 ? nt_max / 4 : 1;
-        if (splits > cap) splits = cap;
+        // The split count that a small timing model likes best (microseconds, fitted to this kernel on the 256-CU
+        // part: ~10 per work-group outside its tile loop, 1.0 per tile of a 4-wave work-group and 1.65 of an 8-wave
+        // one at head_dim 128, work-groups beyond what the chip holds at once run in further rounds; the partials
+        // and the merge kernel cost 2 + S + rows/1024 * (0.9 + 0.13 S)).  Splitting only pays when few work-groups
+        // would otherwise walk a long KV axis; never fewer than 4 KV tiles per split.
+        const WgShape sh = shape_of(d);
+        const double wgs = double(q_tiles_of(d)) * d.batch * d.num_kv_heads;
+        const double resident = 256.0 * (sh.waves == 8 || sh.blocks == 2 ? 1 : 2);
+        const double t_tile = (sh.waves == 8 ? 1.65 : sh.blocks == 2 ? 2.4 : 1.0) * d.head_dim / 128.0;
+        const double rows_k = double(d.total_nodes) * d.num_q_heads / 1024.0;
+        const int cap = nt_max / 4 > 0 ? (nt_max / 4 < 64 ? nt_max / 4 : 64) : 1;
+        double best = 0;
+        for (int s = 1; s <= cap; ++s) {
+            const double rounds = double(int64_t((wgs * s + resident - 1) / resident));
+            const double t = rounds * (10.0 + double((nt_max + s - 1) / s) * t_tile) +
+                             (s > 1 ? 2.0 + s + rows_k * (0.9 + 0.13 * s) : 0.0);
+            if (s == 1 || t < best) {
+                best = t;
+                splits = s;
+            }
+        }
     }
     if (splits > nt_max) splits = nt_max;
     if (splits < 1) splits = 1;
