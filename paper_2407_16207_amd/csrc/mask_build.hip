@@ -3,26 +3,29 @@
 // Paper Section 4.1 lets a flattened token attend only to its ancestors; on the merged graph of Section 5.3
 // that set is the closure over all parent edges.  Rows live in LDS as packed 64-bit words and are relaxed
 //     row[i] <- bit(i) | OR_{p in parents(i)} row[p]
-// for all (node, word) items in parallel until nothing changes.  Nodes are in topological order, so the
-// relaxation reaches its (unique) fixed point after at most depth+1 sweeps; the loop is also hard-bounded by
-// the node count, so every wave leaves the kernel.  A sweep costs one LDS round trip and one barrier.
+// level by level: a node takes its parents' rows once they are final.  Nodes are in topological order, so this
+// ends after depth+1 sweeps; the loop is also hard-bounded by the node count, so every wave leaves the kernel.  One thread per node holds the node's whole row (W words) and its first four
+// parent ids in registers; a sweep is four narrow LDS reads (are my parents final?), the wide reads of the
+// parents' rows once per node, and one barrier of a work-group as large as the sequence.
 #include "gsd_internal.h"
 
 namespace gsd {
 
-constexpr int kMaskThreads = 1024;
 constexpr int kEdgeCacheInts = 6144;   // per-sequence parent lists are staged in LDS when they fit
 
-__global__ __launch_bounds__(kMaskThreads) void build_mask_kernel(
+template <int W>
+__global__ __launch_bounds__(GSD_MAX_NODES_PER_SEQ) void build_mask_kernel(
     int32_t max_nodes, int32_t words_per_row, const int32_t *__restrict__ node_offsets,
-    const int32_t *__restrict__ parent_offsets, const int32_t *__restrict__ parent_idx,
-    uint64_t *__restrict__ mask, int32_t *__restrict__ dag_error_flag) {
-    extern __shared__ uint64_t rows[];                       // [n][W]
+    const int32_t *__restrict__ parent_offsets, const int32_t *__restrict__ parent_idx, uint64_t *__restrict__ mask,
+    int32_t *__restrict__ dag_error_flag) {
+    __shared__ __attribute__((aligned(16))) uint64_t rows[GSD_MAX_NODES_PER_SEQ * W];     // [n][W]
     __shared__ int32_t edge_cache[kEdgeCacheInts];
     __shared__ int32_t off_cache[GSD_MAX_NODES_PER_SEQ + 1];
+    __shared__ int32_t done_at[GSD_MAX_NODES_PER_SEQ + 1];
+    __shared__ int changed_flag[3];
 
     const int b = blockIdx.x;
-    const int W = words_per_row;
+    const int threads = blockDim.x;                          // >= max_nodes: one node per thread
     const int64_t base = node_offsets[b];
     int n = node_offsets[b + 1] - node_offsets[b];
     bool bad = false;
@@ -31,97 +34,134 @@ __global__ __launch_bounds__(kMaskThreads) void build_mask_kernel(
         bad = true;
     }
     if (n <= 0) return;
-    const int items = n * W;
     const int32_t e0 = parent_offsets[base];
     const int32_t e1 = parent_offsets[base + n];
     const bool cached = (e1 - e0) <= kEdgeCacheInts;
 
-    for (int i = threadIdx.x; i <= n; i += kMaskThreads) off_cache[i] = parent_offsets[base + i] - e0;
+    for (int i = threadIdx.x; i <= n; i += threads) off_cache[i] = parent_offsets[base + i] - e0;
     if (cached)
-        for (int e = threadIdx.x; e < e1 - e0; e += kMaskThreads) edge_cache[e] = parent_idx[e0 + e];
-    for (int idx = threadIdx.x; idx < items; idx += kMaskThreads) {
-        const int i = idx / W, w = idx - i * W;
-        rows[idx] = (w == (i >> 6)) ? (uint64_t(1) << (i & 63)) : uint64_t(0);
-    }
-    __syncthreads();
-    const int32_t *edges = cached ? edge_cache : (parent_idx + e0);
-
-    // Each thread owns up to kItemsPerThread (node, word) items and keeps the first kRegParents parent ids of
-    // each in registers, so a sweep is a handful of independent LDS reads; convergence is signalled through three
-    // rotating LDS flags (set in sweep s, read after its barrier, cleared during sweep s+1 for sweep s+2).
-    constexpr int kItemsPerThread = (GSD_MAX_NODES_PER_SEQ * 8 + kMaskThreads - 1) / kMaskThreads;   // 4096 words max
-    constexpr int kRegParents = 4;
-    int item_node[kItemsPerThread], item_word[kItemsPerThread], item_deg[kItemsPerThread];
-    int item_par[kItemsPerThread][kRegParents];
-#pragma unroll
-    for (int q = 0; q < kItemsPerThread; ++q) {
-        const int idx = threadIdx.x + q * kMaskThreads;
-        item_node[q] = -1;
-        item_word[q] = 0;
-        item_deg[q] = 0;
-#pragma unroll
-        for (int x = 0; x < kRegParents; ++x) item_par[q][x] = -1;
-        if (idx < items) {
-            const int i = idx / W;
-            item_node[q] = i;
-            item_word[q] = idx - i * W;
-            const int e_lo = off_cache[i], e_hi = off_cache[i + 1];
-            item_deg[q] = e_hi - e_lo;
-#pragma unroll
-            for (int x = 0; x < kRegParents; ++x) {
-                if (e_lo + x < e_hi) {
-                    const int pp = edges[e_lo + x];
-                    if (pp >= 0 && pp < i) item_par[q][x] = pp;
-                    else if (pp != -1) bad = true;
-                }
-            }
-        }
-    }
-    __shared__ int changed_flag[3];
+        for (int e = threadIdx.x; e < e1 - e0; e += threads) edge_cache[e] = parent_idx[e0 + e];
     if (threadIdx.x < 3) changed_flag[threadIdx.x] = 0;
     __syncthreads();
 
-    for (int sweep = 0; sweep <= n; ++sweep) {
-        bool changed = false;
+    const int i = threadIdx.x;
+    const bool active = i < n;
+    constexpr int kRegParents = 4;
+    // The first four parents live in registers as two indices each, so that a sweep's reads carry no branches (a
+    // branch per parent serialises the LDS round trips): an absent parent reads the node's own row (OR-ing it in
+    // changes nothing) and slot n of done_at, which is final from the start.
+    int par_row[kRegParents], par_done[kRegParents];
+    int e_lo = 0, e_hi = 0;
+    uint64_t r[W];
 #pragma unroll
-        for (int q = 0; q < kItemsPerThread; ++q) {
-            const int i = item_node[q];
-            if (i < 0) continue;
-            const int w = item_word[q];
-            const int idx = i * W + w;
-            const uint64_t cur = rows[idx];
-            uint64_t acc = cur;
+    for (int w = 0; w < W; ++w) r[w] = 0;
 #pragma unroll
-            for (int x = 0; x < kRegParents; ++x)
-                if (item_par[q][x] >= 0) acc |= rows[item_par[q][x] * W + w];
-            for (int e = off_cache[i] + kRegParents; e < off_cache[i] + item_deg[q]; ++e) {   // rare: more parents
-                const int pp = edges[e];
-                if (pp >= 0 && pp < i) acc |= rows[pp * W + w];
-                else if (pp != -1) bad = true;
+    for (int x = 0; x < kRegParents; ++x) {
+        par_row[x] = active ? i : 0;
+        par_done[x] = n;
+    }
+    // parent e of this sequence, from the LDS copy or (sequences with more edges than the cache holds) from memory
+    auto edge_at = [&](int e) -> int { return cached ? edge_cache[e] : parent_idx[e0 + e]; };
+    if (active) {
+        e_lo = off_cache[i];
+        e_hi = off_cache[i + 1];
+#pragma unroll
+        for (int x = 0; x < kRegParents; ++x) {
+            if (e_lo + x < e_hi) {
+                const int pp = edge_at(e_lo + x);
+                if (pp >= 0 && pp < i) {
+                    par_row[x] = pp;
+                    par_done[x] = pp;
+                } else if (pp != -1) {
+                    bad = true;
+                }
             }
-            if (acc != cur) {
-                rows[idx] = acc;
-                changed = true;
+        }
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+            r[w] = (w == (i >> 6)) ? (uint64_t(1) << (i & 63)) : uint64_t(0);
+            rows[i * W + w] = r[w];
+        }
+        done_at[i] = 0x7fffffff;
+    }
+    if (threadIdx.x == 0) done_at[n] = -1;
+    __syncthreads();
+    const bool more = active && e_hi - e_lo > kRegParents;     // rare: a node with more than four parents
+
+    // Level-synchronous: a node takes its parents' rows once, in the first sweep that finds all of them final
+    // (done_at[p] = sweep in which row p became final, compared against the current sweep so that only rows
+    // finished before the last barrier count), and is final itself from then on.  Sweep s finishes the nodes at
+    // depth s; the others spend four narrow LDS reads.  Nodes are in topological order, so the lowest unfinished
+    // node is always ready: a sweep that finishes nothing means everything is finished.  That is signalled through
+    // three rotating LDS flags: set in sweep s, read after its barrier, cleared during sweep s+1 for sweep s+2.
+    bool mine_done = !active;
+    for (int sweep = 0; sweep <= n; ++sweep) {
+        bool finished = false;
+        if (!mine_done) {
+            bool ready = true;
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) ready &= done_at[par_done[x]] < sweep;
+            if (more) {
+                for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                    const int pp = edge_at(e);
+                    if (pp >= 0 && pp < i) ready &= done_at[pp] < sweep;
+                    else if (pp != -1) bad = true;
+                }
+            }
+            if (ready) {
+#pragma unroll
+                for (int x = 0; x < kRegParents; ++x)
+#pragma unroll
+                    for (int w = 0; w < W; ++w) r[w] |= rows[par_row[x] * W + w];
+                if (more) {
+                    for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                        const int pp = edge_at(e);
+                        if (pp >= 0 && pp < i) {
+#pragma unroll
+                            for (int w = 0; w < W; ++w) r[w] |= rows[pp * W + w];
+                        }
+                    }
+                }
+#pragma unroll
+                for (int w = 0; w < W; ++w) rows[i * W + w] = r[w];
+                done_at[i] = sweep;
+                mine_done = true;
+                finished = true;
             }
         }
         const int slot = sweep % 3;
-        if (changed) changed_flag[slot] = 1;
+        if (finished) changed_flag[slot] = 1;
         if (threadIdx.x == 0) changed_flag[(sweep + 1) % 3] = 0;
         __syncthreads();
         if (changed_flag[slot] == 0) break;       // uniform: everybody reads the same flag after the barrier
     }
 
-    uint64_t *out = mask + base * W;
-    for (int idx = threadIdx.x; idx < items; idx += kMaskThreads) out[idx] = rows[idx];
+    if (active) {
+        uint64_t *out = mask + (base + i) * words_per_row;
+#pragma unroll
+        for (int w = 0; w < W; ++w) out[w] = r[w];
+        for (int w = W; w < words_per_row; ++w) out[w] = 0;   // rows wider than any node id can reach
+    }
     if (bad && dag_error_flag) *dag_error_flag = 1;
 }
 
 hipError_t launch_build_mask(int32_t batch, int32_t max_nodes, int32_t words_per_row, const int32_t *node_offsets,
                              const int32_t *parent_offsets, const int32_t *parent_idx, uint64_t *mask,
                              int32_t *dag_error_flag, hipStream_t stream) {
-    const size_t lds = size_t(max_nodes) * words_per_row * sizeof(uint64_t);
-    hipLaunchKernelGGL(build_mask_kernel, dim3(batch), dim3(kMaskThreads), lds, stream, max_nodes, words_per_row,
-                       node_offsets, parent_offsets, parent_idx, mask, dag_error_flag);
+    const dim3 grid(batch), block((max_nodes + 63) / 64 * 64);
+#define GSD_MASK_CASE(WORDS)                                                                                         \
+    case WORDS:                                                                                                      \
+        hipLaunchKernelGGL(build_mask_kernel<WORDS>, grid, block, 0, stream, max_nodes, words_per_row, node_offsets,  \
+                           parent_offsets, parent_idx, mask, dag_error_flag);                                        \
+        break;
+    // words computed per row: no node id reaches past word GSD_MAX_NODES_PER_SEQ/64 - 1, wider rows are zero-filled
+    static_assert(GSD_MAX_NODES_PER_SEQ == 512, "the cases below cover 512 / 64 = 8 words");
+    switch (words_per_row < 8 ? words_per_row : 8) {
+        GSD_MASK_CASE(1) GSD_MASK_CASE(2) GSD_MASK_CASE(3) GSD_MASK_CASE(4)
+        GSD_MASK_CASE(5) GSD_MASK_CASE(6) GSD_MASK_CASE(7) GSD_MASK_CASE(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef GSD_MASK_CASE
     return hipGetLastError();
 }
 
