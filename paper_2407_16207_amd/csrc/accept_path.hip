@@ -22,6 +22,7 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
     __shared__ int32_t pred_s[GSD_MAX_NODES_PER_SEQ];
     __shared__ int32_t tok_s[GSD_MAX_NODES_PER_SEQ];
     __shared__ int32_t path_s[GSD_MAX_NODES_PER_SEQ];
+    __shared__ int32_t back_s[GSD_MAX_NODES_PER_SEQ];
     __shared__ int32_t off_cache[GSD_MAX_NODES_PER_SEQ + 1];
     __shared__ int32_t edge_cache[kAcceptEdgeCache];
     __shared__ uint32_t wave_best[kAcceptThreads / 64];
@@ -46,21 +47,58 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
         tok_s[i] = tokens[base + i];
     }
     __syncthreads();
-    const int32_t *edges = cached ? edge_cache : (parent_idx + e0);
+    // parent e of this sequence, from the LDS copy or (sequences with more edges than the cache holds) from memory
+    auto edge_at = [&](int e) -> int { return cached ? edge_cache[e] : parent_idx[e0 + e]; };
 
+    // One thread per node (kAcceptThreads >= GSD_MAX_NODES_PER_SEQ).  Whether an edge is accepted never changes,
+    // so it is decided once; the first four parents of a node stay in registers as (id, accepted), which leaves a
+    // sweep with four independent LDS reads and no branch per parent (branches serialise the round trips).
+    static_assert(kAcceptThreads >= GSD_MAX_NODES_PER_SEQ, "one thread per node");
+    constexpr int kRegParents = 4;
+    const int i = threadIdx.x;
+    const bool active = i < n;
+    int par[kRegParents];          // parent id; -1 = root; -2 = no such edge, or not accepted
+    int e_lo = 0, e_hi = 0;
+    int32_t my_tok = 0;
+#pragma unroll
+    for (int x = 0; x < kRegParents; ++x) par[x] = -2;
+    // is edge p -> i accepted (p is a well-formed parent of i)?
+    auto accepted = [&](int p) -> bool { return my_tok == (p == -1 ? rp : pred_s[p]); };
+    if (active) {
+        e_lo = off_cache[i];
+        e_hi = off_cache[i + 1];
+        my_tok = tok_s[i];
+#pragma unroll
+        for (int x = 0; x < kRegParents; ++x) {
+            if (e_lo + x < e_hi) {
+                const int p = edge_at(e_lo + x);
+                if (p >= -1 && p < i && accepted(p)) par[x] = p;
+            }
+        }
+    }
+    const bool more = active && e_hi - e_lo > kRegParents;     // rare: a node with more than four parents
+
+    int32_t mine = -1;             // L[i]
     for (int sweep = 0; sweep <= n; ++sweep) {
         int changed = 0;
-        for (int i = threadIdx.x; i < n; i += kAcceptThreads) {
-            const int32_t tok = tok_s[i];
-            int32_t best = L[i];
-            for (int e = off_cache[i]; e < off_cache[i + 1]; ++e) {
-                const int p = edges[e];
-                if (p < -1 || p >= i) continue;
-                const int32_t lp = (p == -1) ? 0 : L[p];
-                const int32_t choice = (p == -1) ? rp : pred_s[p];
-                if (lp >= 0 && tok == choice && lp + 1 > best) best = lp + 1;
+        if (active) {
+            int32_t best = mine;
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) {
+                const int32_t l = L[par[x] >= 0 ? par[x] : i];
+                const int32_t lp = par[x] >= 0 ? l : (par[x] == -1 ? 0 : -1);
+                if (lp >= 0 && lp + 1 > best) best = lp + 1;
             }
-            if (best != L[i]) {
+            if (more) {
+                for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                    const int p = edge_at(e);
+                    if (p < -1 || p >= i || !accepted(p)) continue;
+                    const int32_t lp = (p == -1) ? 0 : L[p];
+                    if (lp >= 0 && lp + 1 > best) best = lp + 1;
+                }
+            }
+            if (best != mine) {
+                mine = best;
                 L[i] = best;
                 changed = 1;
             }
@@ -68,15 +106,30 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
         if (!__syncthreads_or(changed)) break;
     }
 
+    // back pointer of every accepted node: the smallest-id accepted parent that ends a path one node shorter
+    // (the root, id -1, is the smallest)
+    if (active && mine > 0) {
+        int32_t chosen = 0x7fffffff;
+#pragma unroll
+        for (int x = 0; x < kRegParents; ++x) {
+            const int32_t l = L[par[x] >= 0 ? par[x] : i];
+            const int32_t lp = par[x] >= 0 ? l : (par[x] == -1 ? 0 : -1);
+            if (lp == mine - 1 && par[x] < chosen) chosen = par[x];
+        }
+        if (more) {
+            for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                const int p = edge_at(e);
+                if (p < -1 || p >= i || !accepted(p)) continue;
+                const int32_t lp = (p == -1) ? 0 : L[p];
+                if (lp == mine - 1 && p < chosen) chosen = p;
+            }
+        }
+        back_s[i] = chosen;
+    }
+
     // best end node: largest L, then smallest id.  key = L * 1024 + (1023 - i), 0 = nothing accepted.
     uint32_t key = 0;
-    for (int i = threadIdx.x; i < n; i += kAcceptThreads) {
-        const int32_t l = L[i];
-        if (l > 0) {
-            const uint32_t k = uint32_t(l) * 1024u + uint32_t(1023 - i);
-            key = k > key ? k : key;
-        }
-    }
+    if (active && mine > 0) key = uint32_t(mine) * 1024u + uint32_t(1023 - i);
     for (int off = 32; off > 0; off >>= 1) {
         const uint32_t other = __shfl_xor(key, off, 64);
         key = other > key ? other : key;
@@ -91,18 +144,9 @@ __global__ __launch_bounds__(kAcceptThreads) void accept_kernel(
         len_s = len;
         accept_len[b] = len;
         bonus_token[b] = (len > 0) ? pred_s[v] : rp;
-        for (int pos = len - 1; pos >= 0; --pos) {
+        for (int pos = len - 1; pos >= 0 && v >= 0 && v < n; --pos) {   // L drops by one per step: the root's child sits at pos 0
             path_s[pos] = v;
-            int32_t chosen = 0x7fffffff;
-            for (int e = off_cache[v]; e < off_cache[v + 1]; ++e) {
-                const int p = edges[e];
-                if (p < -1 || p >= v) continue;
-                const int32_t lp = (p == -1) ? 0 : L[p];
-                const int32_t choice = (p == -1) ? rp : pred_s[p];
-                if (lp == pos && tok_s[v] == choice && p < chosen) chosen = p;
-            }
-            if (chosen == 0x7fffffff || chosen < 0) break;   // reached the root (pos == 0)
-            v = chosen;
+            v = back_s[v];
         }
     }
     __syncthreads();
