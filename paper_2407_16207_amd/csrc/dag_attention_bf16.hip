@@ -222,26 +222,33 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     uint64_t *my_mask = mask_lds + (wave * RBW * 32 + col) * kMaxWords;
     uint64_t live = 0;
     {
-        uint64_t seen_any[kMaxWords];
-#pragma unroll
-        for (int j = 0; j < kMaxWords; ++j) seen_any[j] = 0;
+        // All words of a row are fetched by unconditional loads (the word index is clamped, the value masked
+        // afterwards): guarded loads become a branch and a full wait per word, eight memory round trips in a row.
+        uint32_t lane_live = 0;          // bit j: a row of this lane sees a node of draft tile j
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
             const uint64_t *mrow = p.mask + (int64_t(node_base) + node_of(rb)) * p.words_per_row;
             const bool ok = row_is_valid(rb);
+            uint64_t words[kMaxWords];
+#pragma unroll
+            for (int j = 0; j < kMaxWords; ++j) words[j] = mrow[min(j, p.words_per_row - 1)];
 #pragma unroll
             for (int j = 0; j < kMaxWords; ++j) {
-                const uint64_t w = (ok && j < ntd) ? mrow[j] : 0;
+                const uint64_t w = (ok && j < ntd) ? words[j] : 0;
                 my_mask[rb * 32 * kMaxWords + j] = w;
-                seen_any[j] |= w;
+                lane_live |= uint32_t(w != 0) << j;
             }
         }
-        for (int j = 0; j < ntd; ++j) {
-            uint64_t w = 0;
+        // one exchange for the whole work-group: every wave publishes which tiles its rows see
+        __shared__ uint32_t wave_live[NW];
+        uint32_t mine = 0;
 #pragma unroll
-            for (int x = 0; x < kMaxWords; ++x) w = (x == j) ? seen_any[x] : w;
-            if (__syncthreads_or(w != 0)) live |= uint64_t(1) << (j & 63);
-        }
+        for (int j = 0; j < kMaxWords; ++j)
+            if (__ballot((lane_live >> j) & 1u)) mine |= 1u << j;
+        if (lane == 0) wave_live[wave] = mine;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) live |= wave_live[w];
     }
     // smallest live tile index > ti inside the split's range, or t_end
     auto next_live = [&](int ti) __attribute__((always_inline)) -> int {
