@@ -122,80 +122,88 @@ hipError_t launch_softmax_stats(int64_t rows, int32_t vocab, int dtype, const vo
 }
 
 constexpr int kStochThreads = 512;
-constexpr int kStochEdgeCache = 6144;
 
 __global__ __launch_bounds__(kStochThreads) void accept_stochastic_kernel(const gsd_stochastic_desc d) {
     __shared__ int32_t L[GSD_MAX_NODES_PER_SEQ];
     __shared__ int32_t path_s[GSD_MAX_NODES_PER_SEQ];
-    __shared__ int32_t off_cache[GSD_MAX_NODES_PER_SEQ + 1];
-    __shared__ int32_t edge_cache[kStochEdgeCache];      // parent id, or INT32_MIN for a rejected / malformed edge
+    __shared__ int32_t back_s[GSD_MAX_NODES_PER_SEQ];
     __shared__ uint32_t wave_best[kStochThreads / 64];
     __shared__ int32_t len_s;
+    static_assert(kStochThreads >= GSD_MAX_NODES_PER_SEQ, "one thread per node");
 
     const int b = blockIdx.x;
     const int64_t base = d.node_offsets[b];
     int n = d.node_offsets[b + 1] - d.node_offsets[b];
     if (n > d.max_nodes) n = d.max_nodes;
     if (n < 0) n = 0;
-    const int32_t e0 = d.parent_offsets[base];
-    const int32_t e1 = d.parent_offsets[base + n];
-    const bool cached = (e1 - e0) <= kStochEdgeCache;    // larger graphs re-test their edges on every sweep
     const float *root_max = d.row_max + d.total_nodes, *root_sum = d.row_sumexp + d.total_nodes;
 
-    // one edge: does the coin of child i pass against the LLM's probability of its token after parent r ?
-    auto edge_passes = [&](int i, int r) -> bool {
-        const int32_t tok = d.tokens[base + i];
-        if (tok < 0 || tok >= d.vocab) return false;     // a token outside the vocabulary is never accepted
-        float logit, mx, sm;
-        if (r == -1) {
-            logit = load_logit(d.root_logits, int64_t(b) * d.row_stride + tok, d.dtype);
-            mx = root_max[b];
-            sm = root_sum[b];
-        } else {
-            logit = load_logit(d.logits, (base + r) * d.row_stride + tok, d.dtype);
-            mx = d.row_max[base + r];
-            sm = d.row_sumexp[base + r];
-        }
-        const float prob = __expf(logit - mx) / sm;
-        return d.accept_u[base + i] * d.draft_prob[base + i] < prob;
+    // One thread per node.  Whether an edge passes never changes, so every node tests its own parent edges once
+    // (its coin against the LLM's probability of its token after that parent) and keeps the first four that pass
+    // in registers; the loads of the four tests are issued together, with clamped indices instead of branches.
+    constexpr int kRegParents = 4;
+    const int i = threadIdx.x;
+    const bool active = i < n;
+    int par[kRegParents];          // parent id of a passing edge; -1 = root; -2 = no such edge, or it did not pass
+#pragma unroll
+    for (int x = 0; x < kRegParents; ++x) par[x] = -2;
+    int32_t e_lo = 0, e_hi = 0;    // this node's slice of parent_idx
+    int32_t tok = 0;
+    bool tok_ok = false;           // a token outside the vocabulary is never accepted
+    float coin = 0.f;              // accept_u * draft_prob: the edge passes iff coin < p_r(tok)
+    // the LLM's probability of this node's token after parent r (a well-formed parent, -1 = the root)
+    auto prob_after = [&](int r) -> float {
+        const void *rows = r == -1 ? d.root_logits : d.logits;
+        const int64_t row = r == -1 ? int64_t(b) : base + r;
+        const float mx = r == -1 ? root_max[b] : d.row_max[base + r];
+        const float sm = r == -1 ? root_sum[b] : d.row_sumexp[base + r];
+        return __expf(load_logit(rows, row * d.row_stride + tok, d.dtype) - mx) / sm;
     };
-
-    for (int i = threadIdx.x; i <= n; i += kStochThreads) off_cache[i] = d.parent_offsets[base + i] - e0;
-    for (int i = threadIdx.x; i < n; i += kStochThreads) L[i] = -1;
-    __syncthreads();
-    if (cached) {
-        // edges are tested once, in parallel over edges: find the child of edge e by binary search over the offsets
-        for (int e = threadIdx.x; e < e1 - e0; e += kStochThreads) {
-            int lo = 0, hi = n;                  // off_cache[lo] <= e < off_cache[hi]
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (off_cache[mid] <= e) lo = mid; else hi = mid;
+    if (active) {
+        e_lo = d.parent_offsets[base + i];
+        e_hi = d.parent_offsets[base + i + 1];
+        tok = d.tokens[base + i];
+        coin = d.accept_u[base + i] * d.draft_prob[base + i];
+        tok_ok = tok >= 0 && tok < d.vocab;
+        if (!tok_ok) tok = 0;                                  // keeps the gathers below in bounds
+        if (e_hi > e_lo) {
+            int r[kRegParents];
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) r[x] = d.parent_idx[min(e_lo + x, e_hi - 1)];
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) {
+                const bool wf = e_lo + x < e_hi && r[x] >= -1 && r[x] < i;
+                const float pr = prob_after(wf ? r[x] : -1);
+                if (wf && tok_ok && coin < pr) par[x] = r[x];
             }
-            const int i = lo;
-            const int r = d.parent_idx[e0 + e];
-            const bool ok = r >= -1 && r < i && edge_passes(i, r);
-            edge_cache[e] = ok ? r : INT32_MIN;
         }
+        L[i] = -1;
     }
+    const bool more = active && e_hi - e_lo > kRegParents;     // rare: a node with more than four parents
+    auto passes = [&](int r) -> bool { return r >= -1 && r < i && tok_ok && coin < prob_after(r); };
     __syncthreads();
 
-    auto edge_parent = [&](int i, int e) -> int {        // accepted parent of edge e of node i, or INT32_MIN
-        if (cached) return edge_cache[e];
-        const int r = d.parent_idx[e0 + e];
-        return (r >= -1 && r < i && edge_passes(i, r)) ? r : INT32_MIN;
-    };
-
+    int32_t mine = -1;             // L[i]
     for (int sweep = 0; sweep <= n; ++sweep) {
         int changed = 0;
-        for (int i = threadIdx.x; i < n; i += kStochThreads) {
-            int32_t best = L[i];
-            for (int e = off_cache[i]; e < off_cache[i + 1]; ++e) {
-                const int r = edge_parent(i, e);
-                if (r == INT32_MIN) continue;
-                const int32_t lr = (r == -1) ? 0 : L[r];
+        if (active) {
+            int32_t best = mine;
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) {
+                const int32_t l = L[par[x] >= 0 ? par[x] : i];
+                const int32_t lr = par[x] >= 0 ? l : (par[x] == -1 ? 0 : -1);
                 if (lr >= 0 && lr + 1 > best) best = lr + 1;
             }
-            if (best != L[i]) {
+            if (more) {
+                for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                    const int r = d.parent_idx[e];
+                    if (!passes(r)) continue;
+                    const int32_t lr = (r == -1) ? 0 : L[r];
+                    if (lr >= 0 && lr + 1 > best) best = lr + 1;
+                }
+            }
+            if (best != mine) {
+                mine = best;
                 L[i] = best;
                 changed = 1;
             }
@@ -203,14 +211,28 @@ __global__ __launch_bounds__(kStochThreads) void accept_stochastic_kernel(const 
         if (!__syncthreads_or(changed)) break;
     }
 
-    uint32_t key = 0;                                    // largest L, then smallest id
-    for (int i = threadIdx.x; i < n; i += kStochThreads) {
-        const int32_t l = L[i];
-        if (l > 0) {
-            const uint32_t k = uint32_t(l) * 1024u + uint32_t(1023 - i);
-            key = k > key ? k : key;
+    // back pointer of every accepted node: the smallest-id passing parent that ends a path one node shorter
+    if (active && mine > 0) {
+        int32_t chosen = 0x7fffffff;
+#pragma unroll
+        for (int x = 0; x < kRegParents; ++x) {
+            const int32_t l = L[par[x] >= 0 ? par[x] : i];
+            const int32_t lr = par[x] >= 0 ? l : (par[x] == -1 ? 0 : -1);
+            if (lr == mine - 1 && par[x] < chosen) chosen = par[x];
         }
+        if (more) {
+            for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                const int r = d.parent_idx[e];
+                if (!passes(r)) continue;
+                const int32_t lr = (r == -1) ? 0 : L[r];
+                if (lr == mine - 1 && r < chosen) chosen = r;
+            }
+        }
+        back_s[i] = chosen;
     }
+
+    uint32_t key = 0;                                    // largest L, then smallest id
+    if (active && mine > 0) key = uint32_t(mine) * 1024u + uint32_t(1023 - i);
     for (int off = 32; off > 0; off >>= 1) {
         const uint32_t other = __shfl_xor(key, off, 64);
         key = other > key ? other : key;
@@ -225,17 +247,9 @@ __global__ __launch_bounds__(kStochThreads) void accept_stochastic_kernel(const 
         len_s = len;
         d.accept_len[b] = len;
         d.end_node[b] = v;
-        for (int pos = len - 1; pos >= 0; --pos) {
+        for (int pos = len - 1; pos >= 0 && v >= 0 && v < n; --pos) {   // L drops by one per step: the root's child sits at pos 0
             path_s[pos] = v;
-            int32_t chosen = 0x7fffffff;
-            for (int e = off_cache[v]; e < off_cache[v + 1]; ++e) {
-                const int r = edge_parent(v, e);
-                if (r == INT32_MIN) continue;
-                const int32_t lr = (r == -1) ? 0 : L[r];
-                if (lr == pos && r < chosen) chosen = r;
-            }
-            if (chosen == 0x7fffffff || chosen < 0) break;
-            v = chosen;
+            v = back_s[v];
         }
     }
     __syncthreads();
