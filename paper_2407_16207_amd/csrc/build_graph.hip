@@ -4,10 +4,14 @@
 // Whether a node exists depends on its parent having been expanded, which depends on the parent not being redundant,
 // which depends on which EARLIER nodes exist: the construction is sequential across layers, so the work-group walks
 // the tree layer by layer (nodes come breadth first: a layer is a run of consecutive ids).  Within a layer everything
-// is parallel: existence comes from the layer above; the first occurrence of a node's tau-gram is found by scanning
-// all earlier existing nodes and comparing the tau tokens along the two ancestor chains exactly (no hashing: at most
-// 512 nodes, so the quadratic scan is a few thousand LDS reads per thread).  A redundant node whose first occurrence
-// lies in its own layer is merged into it: the children of that node get one more parent.
+// is parallel: existence comes from the layer above, and the first occurrence of a node's tau-gram is a lookup.
+// Before the walk every node gets the exact equivalence class of its tau-gram among ALL tree nodes (no hashing):
+// class_t(i) = the smallest j <= i with tok[j] == tok[i] and class_(t-1)(parent j) == class_(t-1)(parent i), built
+// level by level with one all-pairs comparison per level (the candidates of a wave sit one per lane and are
+// broadcast with readlane, so the comparison touches no memory).  During the walk the smallest existing node of
+// every class is kept in a table (atomic min by the layer's existing nodes), so "the earliest existing earlier node
+// with the same tau-gram" is one read.  A redundant node whose first occurrence lies in its own layer is merged
+// into it: the children of that node get one more parent.
 // Two launches: the first only counts nodes and edges per sequence, the second repeats the construction and writes
 // the packed graph behind the sequences before it (the library keeps no scratch memory).
 #include "gsd_internal.h"
@@ -25,6 +29,9 @@ struct GraphLds {
     int32_t merged_to[GSD_MAX_NODES_PER_SEQ];  // first occurrence this node is merged into, or -1
     uint32_t sib_max[GSD_MAX_NODES_PER_SEQ + 1];   // float bits of the largest child probability, slot p+1
     int32_t scan[GSD_MAX_NODES_PER_SEQ];
+    int32_t cls[GSD_MAX_NODES_PER_SEQ];        // class of the node's tau-gram (an earlier-or-equal node id), -1 if none
+    int32_t first_ex[GSD_MAX_NODES_PER_SEQ];   // per class: smallest existing node seen so far
+    int32_t merge_cnt[GSD_MAX_NODES_PER_SEQ];  // nodes merged into this one
     int32_t bad;
     int32_t max_depth;
 };
@@ -49,6 +56,8 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
         s.flags[i] = 0;
         s.merged_to[i] = -1;
     }
+    s.first_ex[i] = 0x7fffffff;
+    s.merge_cnt[i] = 0;
     __syncthreads();
     if (i < n) {
         int p = s.par[i];
@@ -80,11 +89,45 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
     __syncthreads();
     const int max_depth = s.max_depth;
     const int my_depth = i < n ? s.depth[i] : 0;
+
+    // tau-gram classes, level by level.  At level t a node with depth >= t has the key (its token, the level t-1
+    // class of its parent); its class is the smallest node id with the same key.  Wave w holds nodes 64w .. 64w+63
+    // and only ever needs candidates below that, 64 at a time, one per lane.
+    const int lane = i & 63;
+    int my_cls = -1;                                   // class at the level just finished (level 0: everyone alike)
+    const int32_t my_tok = i < n ? s.tok[i] : 0;
+    const int my_par = i < n ? s.par[i] : -2;
+    const int levels = tau <= max_depth ? tau : 0;     // no chain reaches tau nodes: nothing is ever redundant
+    for (int t = 1; t <= levels; ++t) {
+        const int my_prev = t == 1 ? 0 : (my_par >= 0 ? s.cls[my_par] : -1);     // class of the parent one level down
+        const bool my_valid = my_depth >= t;
+        s.scan[i] = my_prev;                           // staged so that the candidates can be fetched one per lane
+        __syncthreads();                               // (also: everyone has read the previous level's classes)
+        int found = my_valid ? i : -1;
+        for (int c0 = 0; c0 <= (i | 63) && c0 < n; c0 += 64) {      // uniform per wave
+            const int j = c0 + lane;
+            const int32_t cand_tok = j < n ? s.tok[j] : 0;
+            const int32_t cand_prev = j < n ? s.scan[j] : -1;
+            const int cand_valid = (j < n && s.depth[j] >= t) ? 1 : 0;
+            for (int l = 0; l < 64; ++l) {
+                const int32_t tj = __builtin_amdgcn_readlane(cand_tok, l);
+                const int32_t pj = __builtin_amdgcn_readlane(cand_prev, l);
+                const int vj = __builtin_amdgcn_readlane(cand_valid, l);
+                const int jj = c0 + l;
+                if (my_valid && vj && jj < found && tj == my_tok && pj == my_prev) found = jj;
+            }
+        }
+        my_cls = found;
+        s.cls[i] = my_cls;
+        __syncthreads();                               // classes of this level published, staging area free again
+    }
+
     for (int layer = 1; layer <= max_depth; ++layer) {
         // existence and the two pruning rules: everything they need is in the layer above
+        bool ex = false;
         if (my_depth == layer) {
             const int p = s.par[i];
-            const bool ex = p == -1 || (p >= 0 && (s.flags[p] & 0x100) && (s.flags[p] & 0xf) == 0);
+            ex = p == -1 || (p >= 0 && (s.flags[p] & 0x100) && (s.flags[p] & 0xf) == 0);
             int f = 0;
             if (ex) {
                 f = 0x100;
@@ -92,29 +135,18 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
                 if (s.q[i] < theta_sib * __uint_as_float(s.sib_max[p + 1])) f |= 2;
             }
             s.flags[i] = f;
+            // redundancy: the earliest existing earlier node with the same tau-gram.  The existing nodes of this layer
+            // enter the table first (their redundancy does not change whether THEY exist, only whether they are
+            // expanded), then every one of them looks its class up.
+            if (ex && layer >= tau) atomicMin(&s.first_ex[my_cls], i);
         }
         __syncthreads();
-        // redundancy: the earliest existing earlier node with the same tau-gram (existence of this layer is known now;
-        // the redundancy of nodes of this layer does not change whether THEY exist, only whether they are expanded)
-        if (my_depth == layer && (s.flags[i] & 0x100) && layer >= tau) {
-            int first = -1;
-            for (int j = 0; j < i && first < 0; ++j) {
-                if (!(s.flags[j] & 0x100) || s.depth[j] < tau) continue;
-                int a = i, c = j;
-                bool same = true;
-                for (int t = 0; t < tau; ++t) {
-                    if (s.tok[a] != s.tok[c]) {
-                        same = false;
-                        break;
-                    }
-                    a = s.par[a];
-                    c = s.par[c];
-                }
-                if (same) first = j;
-            }
-            if (first >= 0) {
+        if (my_depth == layer && ex && layer >= tau) {
+            const int first = s.first_ex[my_cls];
+            if (first < i) {
                 if (s.depth[first] == layer) {
                     s.merged_to[i] = first;
+                    atomicAdd(&s.merge_cnt[first], 1);
                     s.flags[i] |= 4;
                 } else {
                     s.flags[i] |= 4 | 8;
@@ -139,13 +171,10 @@ __device__ int block_scan(int32_t *buf, int value) {
     return buf[i];
 }
 
-// number of parents of existing node i in the graph: its tree parent plus the nodes merged into that parent
+// number of parents of existing node i in the graph beyond its tree parent: the nodes merged into that parent
 __device__ int extra_parents(const GraphLds &s, int n, int i) {
     const int f = s.par[i];
-    if (f < 0) return 0;
-    int cnt = 0;
-    for (int r = f + 1; r < n && s.depth[r] == s.depth[f]; ++r) cnt += (s.merged_to[r] == f);
-    return cnt;
+    return f < 0 ? 0 : s.merge_cnt[f];
 }
 
 __global__ __launch_bounds__(kGraphThreads) void graph_count_kernel(
@@ -241,7 +270,7 @@ __global__ __launch_bounds__(kGraphThreads) void graph_fill_kernel(
             ++e;
         };
         put(f < 0 ? -1 : new_id[f]);
-        if (f >= 0)
+        if (f >= 0 && s.merge_cnt[f] > 0)              // the nodes merged into the parent, in id order
             for (int r = f + 1; r < n && s.depth[r] == s.depth[f]; ++r)
                 if (s.merged_to[r] == f) put(new_id[r]);
         if (over && error_flag) atomicOr(error_flag, 2);
