@@ -283,6 +283,24 @@ def test_softmax_stats_and_stochastic_acceptance(gpu, dtype):
     assert exact >= len(cdfs) - 1
 
 
+def test_stochastic_acceptance_many_parents(gpu):
+    """Nodes with more parents than the kernel keeps in registers (4): accepted paths stay exact."""
+    import paper_2407_16207_amd as gsd
+    rng = np.random.default_rng(77)
+    pr = stochastic_problem(rng, [90, 300, 512], 257, "f32", max_parents=9)
+    assert np.diff(pr["poff"]).max() > 4
+    d = {k: gpu.to_dev(v) for k, v in pr.items() if isinstance(v, np.ndarray) and k not in ("p", "p_root", "q", "q_root")}
+    ln, path, end, bonus, _, _ = gsd.gsd_accept_stochastic(
+        d["node_offsets"], d["poff"], d["pidx"], d["tokens"], d["lp"], d["lp_root"], d["lq"], d["lq_root"],
+        d["draft_prob"], d["accept_u"], d["resample_u"], pr["max_nodes"])
+    torch.cuda.synchronize()
+    rl, rpath, _, _, _ = gsd_next.accept_stochastic(pr["node_offsets"], pr["poff"], pr["pidx"], pr["tokens"], pr["p"],
+                                                    pr["p_root"], pr["draft_prob"], pr["accept_u"], pr["q"],
+                                                    pr["q_root"], pr["resample_u"])
+    assert np.array_equal(ln.cpu().numpy(), rl) and np.array_equal(path.cpu().numpy(), rpath)
+    assert rl.max() > 2
+
+
 def test_stochastic_limits_on_gpu(gpu, ref):
     """Coins at zero accept every edge with positive probability (the graph's deepest path); a one-hot LLM with a
     certain draft reduces to deterministic verification."""

@@ -99,6 +99,27 @@ def test_mask_general_dags_and_edges(gpu, ref):
     assert np.array_equal(got, ref.build_mask(w2.node_offsets, w2.parent_offsets, w2.parent_idx)[0])
 
 
+def test_mask_and_accept_dense_dags(gpu, ref):
+    """Nodes with more parents than the kernels keep in registers (4), and a sequence whose parent lists (more than
+    6144 entries) do not fit the kernels' LDS copy and are read from memory."""
+    for seed, sizes, max_parents in ((5, [40, 200, 512], 9), (6, [512, 300], 40)):
+        rng = np.random.default_rng(seed)
+        w = custom_workload(rng, sizes, [0] * len(sizes), 1, 1, 64, "f32", vocab=6, max_parents=max_parents)
+        per_seq_edges = np.diff(w.parent_offsets[w.node_offsets])
+        assert np.diff(w.parent_offsets).max() > 4
+        if max_parents == 40:
+            assert per_seq_edges.max() > 6144
+        d = gpu.DeviceWorkload(w)
+        got = gpu.mask_to_numpy(d.build_mask())
+        assert np.array_equal(got, ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)[0])
+        pred = rng.integers(0, 6, w.total_nodes).astype(np.int32)
+        ln, path, bonus, _ = d.accept(logits=False, pred=torch.from_numpy(pred).cuda())
+        wl, wp, wb = ref.accept_longest_path(w.node_offsets, w.parent_offsets, w.parent_idx, w.tokens, pred,
+                                             w.root_pred)
+        assert np.array_equal(ln.cpu().numpy(), wl) and np.array_equal(path.cpu().numpy(), wp)
+        assert np.array_equal(bonus.cpu().numpy(), wb)
+
+
 def test_mask_bad_parent_sets_flag(gpu, ref):
     rng = np.random.default_rng(3)
     w = custom_workload(rng, [6], [0], 1, 1, 64, "f32")
