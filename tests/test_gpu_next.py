@@ -242,11 +242,14 @@ def stochastic_problem(rng, sizes, vocab, dtype, max_parents=3, peaked=2.0):
                 resample_u=resample_u, max_nodes=max(sizes))
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_softmax_stats_and_stochastic_acceptance(gpu, dtype):
+@pytest.mark.parametrize("dtype,vocab,sizes", [("f32", 1003, [60, 1, 200, 17, 512, 33]),
+                                               ("bf16", 1003, [60, 1, 200, 17, 512, 33]),
+                                               # 8192: the draw kernel's slices are whole 16-byte runs (its vector path)
+                                               ("f32", 8192, [60, 40, 150, 17, 90, 33]), ("bf16", 8192, [60, 40, 150, 17, 90, 33])])
+def test_softmax_stats_and_stochastic_acceptance(gpu, dtype, vocab, sizes):
     import paper_2407_16207_amd as gsd
-    rng = np.random.default_rng(31 if dtype == "f32" else 32)
-    pr = stochastic_problem(rng, [60, 1, 200, 17, 512, 33], 1003, dtype)
+    rng = np.random.default_rng((31 if dtype == "f32" else 32) + vocab)
+    pr = stochastic_problem(rng, sizes, vocab, dtype)
     d = {k: gpu.to_dev(v) for k, v in pr.items() if isinstance(v, np.ndarray) and k not in ("p", "p_root", "q", "q_root")}
     ln, path, end, bonus, row_max, row_sum = gsd.gsd_accept_stochastic(
         d["node_offsets"], d["poff"], d["pidx"], d["tokens"], d["lp"], d["lp_root"], d["lq"], d["lq_root"],
