@@ -5,8 +5,8 @@
 // the replicas of node i are numbered first[i] .. first[i]+c[i]-1 with first = exclusive prefix sum of c, and the
 // replica reached through parent slot s from the r-th replica of that parent p is
 //     first[i] + (sum of c over the earlier slots) + r,      with tree parent  first[p] + r   (root: -1).
-// So nothing is enumerated: counts are relaxed in LDS until they stop changing (nodes are in topological order,
-// so that takes at most depth+1 sweeps; the loop is hard-bounded by the node count), a scan gives `first`, and
+// So nothing is enumerated: counts are settled in LDS level by level (nodes are in topological order, so that
+// takes depth+1 sweeps; the loop is hard-bounded by the node count), a scan gives `first`, and
 // every tree node below the cap finds its (origin, slot, r) by a binary search and a walk over one parent list.
 // Counts saturate at 2^62, far above any cap, so sums never wrap.
 #include "gsd_internal.h"
@@ -23,35 +23,80 @@ __device__ __forceinline__ uint64_t sat_add(uint64_t a, uint64_t b) {
 
 // Path counts and their exclusive scan for the calling work-group's sequence.  cnt[0..n), first[0..n]; returns
 // true if a malformed edge was met.  All threads of the work-group must call it.
+// Level-synchronous: a node adds up its parents' counts once, in the first sweep that finds all of them final
+// (done_at[p] = sweep in which cnt[p] became final, compared against the current sweep so that only counts
+// finished before the last barrier are used).  The first four parents of a node sit in registers, an absent one
+// reading slot n (final from the start, count 0), so a sweep's reads carry no branch per parent.
 __device__ bool count_paths(int n, int64_t base, const int32_t *__restrict__ parent_offsets,
-                            const int32_t *__restrict__ parent_idx, uint64_t *cnt, uint64_t *first, int *flags) {
+                            const int32_t *__restrict__ parent_idx, uint64_t *cnt /* [n+1] */, uint64_t *first,
+                            int32_t *done_at /* [n+1] */, int *flags) {
+    constexpr int kRegParents = 4;
     const int i = threadIdx.x;
+    const bool active = i < n;
     bool bad = false;
     int e_lo = 0, e_hi = 0;
-    if (i < n) {
+    int par[kRegParents];                                  // slot in cnt / done_at: a parent id, or n
+    uint64_t roots = 0;                                    // edges from the root among the first four
+#pragma unroll
+    for (int x = 0; x < kRegParents; ++x) par[x] = n;
+    if (active) {
         e_lo = parent_offsets[base + i];
         e_hi = parent_offsets[base + i + 1];
+        if (e_hi > e_lo) {
+            int p[kRegParents];
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) p[x] = parent_idx[min(e_lo + x, e_hi - 1)];
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) {
+                if (e_lo + x >= e_hi) continue;
+                if (p[x] == -1) roots += 1;
+                else if (p[x] >= 0 && p[x] < i) par[x] = p[x];
+                else bad = true;
+            }
+        }
         cnt[i] = 0;
+        done_at[i] = 0x7fffffff;
+    }
+    if (i == 0) {
+        cnt[n] = 0;
+        done_at[n] = -1;
     }
     if (i < 3) flags[i] = 0;
     __syncthreads();
+    const bool more = active && e_hi - e_lo > kRegParents;     // rare: a node with more than four parents
+    bool mine_done = !active;
     for (int sweep = 0; sweep <= n; ++sweep) {
-        bool changed = false;
-        if (i < n) {
-            uint64_t acc = 0;
-            for (int e = e_lo; e < e_hi; ++e) {
-                const int p = parent_idx[e];
-                if (p == -1) acc = sat_add(acc, 1);
-                else if (p >= 0 && p < i) acc = sat_add(acc, cnt[p]);
-                else bad = true;
+        bool finished = false;
+        if (!mine_done) {
+            bool ready = true;
+#pragma unroll
+            for (int x = 0; x < kRegParents; ++x) ready &= done_at[par[x]] < sweep;
+            if (more) {
+                for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                    const int p = parent_idx[e];
+                    if (p >= 0 && p < i) ready &= done_at[p] < sweep;
+                }
             }
-            if (acc != cnt[i]) {
+            if (ready) {
+                uint64_t acc = roots;
+#pragma unroll
+                for (int x = 0; x < kRegParents; ++x) acc = sat_add(acc, cnt[par[x]]);
+                if (more) {
+                    for (int e = e_lo + kRegParents; e < e_hi; ++e) {
+                        const int p = parent_idx[e];
+                        if (p == -1) acc = sat_add(acc, 1);
+                        else if (p >= 0 && p < i) acc = sat_add(acc, cnt[p]);
+                        else bad = true;
+                    }
+                }
                 cnt[i] = acc;
-                changed = true;
+                done_at[i] = sweep;
+                mine_done = true;
+                finished = true;
             }
         }
         const int slot = sweep % 3;
-        if (changed) flags[slot] = 1;
+        if (finished) flags[slot] = 1;
         if (i == 0) flags[(sweep + 1) % 3] = 0;
         __syncthreads();
         if (flags[slot] == 0) break;                      // uniform: read after the barrier
@@ -74,8 +119,9 @@ __device__ bool count_paths(int n, int64_t base, const int32_t *__restrict__ par
 __global__ __launch_bounds__(kUnmergeThreads) void unmerge_count_kernel(
     int32_t max_nodes, const int32_t *__restrict__ node_offsets, const int32_t *__restrict__ parent_offsets,
     const int32_t *__restrict__ parent_idx, int64_t *__restrict__ path_count, int32_t *__restrict__ dag_error_flag) {
-    __shared__ uint64_t cnt[kUnmergeThreads];
+    __shared__ uint64_t cnt[kUnmergeThreads + 1];
     __shared__ uint64_t first[kUnmergeThreads + 1];
+    __shared__ int32_t done_at[kUnmergeThreads + 1];
     __shared__ int flags[3];
     const int b = blockIdx.x;
     const int64_t base = node_offsets[b];
@@ -86,7 +132,7 @@ __global__ __launch_bounds__(kUnmergeThreads) void unmerge_count_kernel(
         bad = true;
     }
     if (n < 0) n = 0;
-    bad |= count_paths(n, base, parent_offsets, parent_idx, cnt, first, flags);
+    bad |= count_paths(n, base, parent_offsets, parent_idx, cnt, first, done_at, flags);
     if (threadIdx.x == 0) path_count[b] = int64_t(first[n]);
     if (bad && dag_error_flag) *dag_error_flag = 1;
 }
@@ -96,8 +142,9 @@ __global__ __launch_bounds__(kUnmergeThreads) void unmerge_fill_kernel(
     const int32_t *__restrict__ parent_offsets, const int32_t *__restrict__ parent_idx,
     const int64_t *__restrict__ path_count, int32_t *__restrict__ tree_node_offsets,
     int32_t *__restrict__ tree_parent, int32_t *__restrict__ tree_parent_offsets, int32_t *__restrict__ tree_origin) {
-    __shared__ uint64_t cnt[kUnmergeThreads];
+    __shared__ uint64_t cnt[kUnmergeThreads + 1];
     __shared__ uint64_t first[kUnmergeThreads + 1];
+    __shared__ int32_t done_at[kUnmergeThreads + 1];
     __shared__ int flags[3];
     __shared__ int wave_sum[kUnmergeThreads / 64];
     const int b = blockIdx.x;
@@ -118,7 +165,7 @@ __global__ __launch_bounds__(kUnmergeThreads) void unmerge_fill_kernel(
     int n = node_offsets[b + 1] - node_offsets[b];
     if (n > max_nodes) n = max_nodes;
     if (n < 0) n = 0;
-    count_paths(n, base, parent_offsets, parent_idx, cnt, first, flags);
+    count_paths(n, base, parent_offsets, parent_idx, cnt, first, done_at, flags);
     const uint64_t total = first[n];
     const int n_tree = int(total < uint64_t(max_tree_nodes) ? total : uint64_t(max_tree_nodes));
 
