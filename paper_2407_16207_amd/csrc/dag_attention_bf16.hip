@@ -3,8 +3,8 @@
 //
 // Shape of the work.  All G = Hq/Hkv query heads of a KV head share its K/V rows and (per node) the same mask
 // row, so the (node, head) pairs of one (sequence, KV head) are packed into one row space r = node*G + g and
-// cut into tiles of 128 rows; a work-group of 4 wavefronts owns one tile (32 rows per wave) and walks the KV
-// axis in tiles of 64 keys: first the prefix tiles (no mask arithmetic, only the ragged last tile is bounded),
+// cut into tiles of 256 rows (128 when a group has fewer than 256); a work-group of 8 (4) wavefronts owns one tile
+// (32 rows per wave) and walks the KV axis in tiles of 64 keys: first the prefix tiles (no mask arithmetic, only the ragged last tile is bounded),
 // then the draft tiles, one 64-bit mask word per row per tile; a draft tile whose word is zero for every row
 // of the work-group is skipped outright.
 //
