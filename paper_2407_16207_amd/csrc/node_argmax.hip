@@ -58,6 +58,7 @@ __global__ __launch_bounds__(THREADS) void node_argmax_kernel(int32_t vocab, con
     // first chunk that holds the lane's maximum; NaN loses every v_max and every compare.
     float body_max = -__builtin_inff();
     int body_chunk = -1;
+    u32x4 body_words = {0, 0, 0, 0};
     auto chunk_values = [&](const u32x4 w, float (&x)[PER_VEC]) {
         if (BF16) {
 #pragma unroll
@@ -81,11 +82,12 @@ __global__ __launch_bounds__(THREADS) void node_argmax_kernel(int32_t vocab, con
         if (m > body_max || (body_chunk < 0 && m == body_max)) {
             body_max = m;
             body_chunk = c;
+            body_words = w;      // kept in registers: fetching the chunk again at the end is a memory round trip per row
         }
     }
     if (body_chunk >= 0) {
         float x[PER_VEC];
-        chunk_values(vec[body_chunk], x);
+        chunk_values(body_words, x);
 #pragma unroll
         for (int j = PER_VEC - 1; j >= 0; --j)
             if (x[j] == body_max) consider(best, x[j], head + body_chunk * PER_VEC + j);
