@@ -74,7 +74,28 @@ def cpu_baseline(w, sample_nodes: int):
     gsd_ref.accept_longest_path(w.node_offsets, w.parent_offsets, w.parent_idx, w.tokens, pred, w.root_pred)
     t_accept = time.perf_counter() - t0
     total = t_attn + t_argmax + (t_mask + t_accept) * S / T
+    # the literal definition on one core: the same oracle on a sixteenth of the sample with OpenMP held to one thread
+    single = None
+    try:
+        import ctypes
+        omp = ctypes.CDLL("libgomp.so.1")
+        threads = gsd_ref.num_threads()
+        S1 = max(1, S // 16)
+        omp.omp_set_num_threads(1)
+        try:
+            t0 = time.perf_counter()
+            gsd_ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale,
+                                  rows=(rb[:S1 * H], ri[:S1 * H], rh[:S1 * H]))
+            gsd_ref.node_argmax(np.ascontiguousarray(w.logits[nodes[:S1]]))
+            t1 = time.perf_counter() - t0
+        finally:
+            omp.omp_set_num_threads(threads)
+        single = {"value": S1 / (t1 + (t_mask + t_accept) * S1 / T), "unit": "nodes/s", "cores": 1,
+                  "sample": f"{S1} draft nodes, {t1:.1f} s"}
+    except OSError:
+        pass
     return {"value": S / total, "unit": "nodes/s", "cores": gsd_ref.num_threads(), "kind": "oracle",
+            "single_thread": single,
             "sample": f"{S} of {T} draft nodes (all {H} heads) for attention+argmax, {t_attn + t_argmax:.1f} s; "
                       f"mask and acceptance on the full batch, scaled by {S}/{T}",
             "seconds": {"mask_full": t_mask, "attention_sample": t_attn, "argmax_sample": t_argmax,
