@@ -9,12 +9,16 @@
 // of the work-group is skipped outright.
 //
 // Matrix-core mapping (v_mfma_f32_32x32x16_bf16, fp32 accumulate).  Scores are computed TRANSPOSED,
-// S^T = K . Q^T, so that a lane owns one query row (column n = lane%32) and 16 keys per 32-key block: row
-// max and row sum are in-lane loops plus one exchange between the wave's halves, and the running rescale
-// factor is a per-lane scalar for the O^T = V^T . P^T accumulators, which have the same column ownership.  The
-// S^T accumulator registers are converted to bf16 in place and fed straight back as the B operand of the
-// second contraction: K rows sit in LDS in the order that makes each lane's 8 consecutive accumulator
-// registers 8 consecutive keys.
+// S^T = K . Q^T, so that a lane owns one query row (column n = lane%32) and 16 keys per 32-key block: the row sum
+// is an in-lane loop plus one exchange between the wave's halves, and a rescale factor is a per-lane scalar for
+// the O^T = V^T . P^T accumulators, which have the same column ownership.  The S^T accumulator registers are
+// converted to bf16 and fed straight back as the B operand of the second contraction: K rows sit in LDS in the
+// order that makes each lane's 8 consecutive accumulator registers 8 consecutive keys.
+//
+// Softmax.  softmax_scale is applied in fp32 to the raw dot products (one fused multiply-add per score, which also
+// subtracts the row's offset).  No running max is kept: the offset is set by the first tile and then only watched
+// through the tile sums; see kSumRaise below.  Rows whose scores leave the range that scheme can follow are computed
+// again, exactly, at the end of the kernel.
 //
 // Data movement.  K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane,
 // no register staging); both are double-buffered.  Rows keep their 16-byte chunks XOR-swizzled (K by row%16, V
@@ -45,7 +49,15 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kKeysPerTile = 64;     // keys per KV tile = one mask word
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kMInit = -1e30f;     // finite stand-in for -inf: the offset stored for a partial without any visible key
-constexpr float kLazyMax = 8.0f;     // a row's offset follows its running max only once a score exceeds it by this much (log2)
+// A row's offset is not its running max: it is a guess (the true max of the first tile) that is corrected only when
+// a tile's probabilities leave a harmless range.  Per lane, the 32 probabilities of a tile add up to less than
+// kSumRaise whenever none of its shifted scores exceeds 9 (log2); a larger sum raises the offset for the tiles that
+// follow.  A sum that is not below kSumPoison (a score more than ~64 above the offset, an overflow, a NaN) or a row
+// total below kSumTiny (an offset more than ~64 above every score) cannot be trusted in fp32: such a row is flagged
+// and computed again by the exact, slow path of the epilogue.
+constexpr float kSumRaise = 16384.0f;
+constexpr float kSumPoison = 0x1p64f;
+constexpr float kSumTiny = 0x1p-64f;
 
 struct AttnParams {
     const __bf16 *q;
@@ -65,7 +77,6 @@ struct AttnParams {
     int32_t splits;
     int32_t wg_per_xcd; // ceil(batch * num_kv_heads / 8) * q_tiles * splits
     float scale_log2e;  // softmax_scale * log2(e)
-    float scale;
 };
 
 template <int D>
@@ -123,8 +134,8 @@ __device__ __forceinline__ void wg_barrier() {
 __device__ __forceinline__ void mfma_v_acc(floatx16 &acc, const bf16x8 &a, const bf16x8 &b) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));
 }
-__device__ __forceinline__ void mfma_v_init(floatx16 &acc, const bf16x8 &a, const bf16x8 &b, const floatx16 &c) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=v"(acc) : "v"(a), "a"(b), "v"(c));   // C and D share a file
+__device__ __forceinline__ void mfma_v_init(floatx16 &acc, const bf16x8 &a, const bf16x8 &b) {   // starts a chain from zero
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=v"(acc) : "v"(a), "a"(b));
 }
 __device__ __forceinline__ void mfma_a_acc(floatx16 &acc, const bf16x8 &a, const bf16x8 &b) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
@@ -268,12 +279,6 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         const __bf16 *qp = p.q + (int64_t(node_base) + node_of(rb)) * p.q_ts + int64_t(head_of(rb)) * p.q_hs + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qf[rb][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 16);
-        // Fold softmax_scale*log2(e) into Q once (rounded back to bf16), so that the matrix pipe delivers the
-        // exponent of 2 directly and the vector ALU spends no multiply per score.
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int z = 0; z < 8; ++z) qf[rb][ks][z] = (__bf16)((float)qf[rb][ks][z] * p.scale_log2e);
         // resident in the accumulator file from here on (otherwise each use copies its fragment over again)
         if (ASM_MFMA) {
 #pragma unroll
@@ -288,27 +293,30 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         for (int i = 0; i < MBD; ++i)
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc_o[rb][i][j] = 0.f;
-    // Scores leave the matrix pipe already in the exponent's domain and already shifted: the first matrix
-    // instruction of every score block accumulates onto m_vec, sixteen copies of -m_run.  m_run is the row's
-    // offset, not its exact running max: it is raised only when a score exceeds it by more than kLazyMax (softmax
-    // does not care which offset is used, and 2^8 is nowhere near the range of fp32 or bf16), so in the steady
-    // state no rescaling and no per-score subtraction happens at all.
-    float m_run[RBW];          // offset (log2 domain) applied to the tile whose scores are held
-    bool m_set[RBW];           // the offset has been taken from real scores (the first visible key sets it)
-    floatx16 m_vec[RBW];
+    // Softmax state of a row.  The matrix pipe delivers raw dot products; one fused multiply-add per score applies
+    // softmax_scale*log2(e) in fp32 and subtracts the row's offset, and the result goes straight into exp2.  Any
+    // offset gives the same softmax, so no running max is kept: the offset is set from the first tile and afterwards
+    // only the sum of each tile's probabilities is looked at (one compare per tile).  When it has grown large the
+    // wave takes a rare branch that touches scalars only: the offset goes up by the sum's exponent for the tiles that
+    // follow, the running sum is rescaled, and the factor is parked for the output accumulators, which are multiplied
+    // once the tile in flight has been added to them.  What this cannot handle (see kSumPoison, kSumTiny) flags the row.
+    float nm[RBW];             // minus the row's offset (log2 domain)
     float l_run[RBW];          // this lane's share of the running sum (the other half lives in lane^32)
-    float alpha[RBW];          // pending rescale of acc_o / l_run for the tile whose scores are held
-    bool need_rescale[RBW];    // wave-uniform: some lane's max moved
+    float sum_carry[RBW];      // sum of the held tile's probabilities converted so far (those taken in phase B)
+    float alpha_now[RBW];      // factor for the output accumulators, due at the start of the next phase B
+    float alpha_next[RBW];     // the same, due one phase B later (the tile whose sum tripped is still to be added)
+    bool poison[RBW];          // per lane: this row needs the exact path
+    bool pend_now = false, pend_next = false;      // wave-uniform: something other than one is parked there
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
-        m_run[rb] = 0.f;
-        m_set[rb] = false;
+        nm[rb] = 0.f;
         l_run[rb] = 0.f;
-        alpha[rb] = 1.f;
-        need_rescale[rb] = false;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) m_vec[rb][j] = 0.f;
+        sum_carry[rb] = 0.f;
+        alpha_now[rb] = 1.f;
+        alpha_next[rb] = 1.f;
+        poison[rb] = false;
     }
+    const float c_log2 = p.scale_log2e;
 
     // ---- global -> LDS copies of K/V tiles ----------------------------------------------------------------------
     // Copy j of this wave fills LDS rows (wave*IPW + j)*RPI .. +RPI-1 of the tile buffer; lane l lands in row
@@ -425,51 +433,46 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 if (!((vis >> key) & 1)) sc[mb][i] = -__builtin_inff();
             }
     };
-    // end of the running-max update for the tile whose in-lane max is mx
-    // mx: in-lane max of the tile's shifted scores `sc`.  Moves the offset where it has to (rarely), fixing up this
-    // tile's scores, the running sum and m_vec; the accumulators are rescaled by the caller (need_rescale, alpha).
-    // Two parts, so that the caller can put a matrix instruction or two between them: the decision (a chain of
-    // dependent vector, scalar and compare instructions; plain bit operations on the lane masks, no branches), and the
-    // rarely taken fix-up behind a wave-uniform branch.
-    bool grow[RBW];
-    float mx_tile[RBW];
-    auto decide_max = [&](float mx, int rb) __attribute__((always_inline)) {
-        mx = max_across_halves(mx);
-        const bool seen = mx > -__builtin_inff();
-        grow[rb] = seen & ((mx > kLazyMax) | !m_set[rb]);
-        m_set[rb] = m_set[rb] | seen;
-        need_rescale[rb] = __any(grow[rb]);
-        mx_tile[rb] = mx;
-    };
-    auto apply_max = [&](floatx16 (&sc)[2], int rb) __attribute__((always_inline)) {
-        alpha[rb] = 1.f;
-        if (need_rescale[rb]) {
-            const float delta = grow[rb] ? mx_tile[rb] : 0.f;
-            m_run[rb] += delta;
-            alpha[rb] = __builtin_amdgcn_exp2f(-delta);
-            l_run[rb] *= alpha[rb];
+    // The first tile sets the offset: the max of its raw (masked) scores, in the exponent's units.  A row that sees
+    // no key of this tile keeps the guess 0.
+    auto first_offset = [&](floatx16 (&sc)[2], int rb) __attribute__((always_inline)) {
+        float mx0 = -__builtin_inff(), mx1 = -__builtin_inff();
 #pragma unroll
-            for (int j = 0; j < 16; ++j) m_vec[rb][j] = -m_run[rb];
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) sc[mb][j] -= delta;
+        for (int e = 0; e < 32; e += 4) {
+            mx0 = max3(mx0, sc[e / 16][e % 16], sc[(e + 1) / 16][(e + 1) % 16]);
+            mx1 = max3(mx1, sc[(e + 2) / 16][(e + 2) % 16], sc[(e + 3) / 16][(e + 3) % 16]);
         }
+        const float mx = max_across_halves(fmaxf(mx0, mx1));
+        nm[rb] = mx > -__builtin_inff() ? -(mx * c_log2) : 0.f;
+    };
+    // The rare branch after a tile whose sum `tot` tripped in some lane of the wave.  Per row (both halves of the
+    // wave agree on everything decided here): a sum that cannot be trusted flags the row; otherwise a large sum
+    // raises the offset by its exponent, for the tiles that follow.  Adds the tile's sum to the running sum.
+    auto adjust = [&](float tot, int rb) __attribute__((always_inline)) {
+        const bool bad_here = !(tot < kSumPoison);
+        const auto sw = __builtin_amdgcn_permlane32_swap(uint32_t(bad_here), uint32_t(bad_here), false, false);
+        poison[rb] = poison[rb] | (sw[0] | sw[1]) != 0;
+        const float big = max_across_halves(bad_here ? 0.f : tot);
+        const float delta = big < kSumRaise ? 0.f : float(__builtin_amdgcn_frexp_expf(big));   // big < 2^delta
+        const float alpha = __builtin_amdgcn_exp2f(-delta);                                    // exact, 1 if nothing moves
+        nm[rb] -= delta;
+        l_run[rb] = (l_run[rb] + (bad_here ? 0.f : tot)) * alpha;
+        alpha_next[rb] = alpha;
     };
 
     // ---- the software pipeline ---------------------------------------------------------------------------------
     // Live tiles are taken in order i = 0, 1, ...; at the top of step i
-    //   registers   shifted (masked) scores of tile i, with m_run / alpha already updated for it, and the first four
-    //               K fragments of tile i+1
+    //   registers   raw (masked) scores of tile i, the first B_SCORES of each lane already converted with the row's
+    //               offset, and the first four K fragments of tile i+1
     //   LDS         K(i+1) in K buffer (i+1)&1 and V(i) in V buffer i&1, complete and published
     //   in flight   the copy of K(i+2) -> K buffer i&1 (V(i+1) is issued during phase A)
-    // Step i:  [rescale acc_o if the max moved]
-    //          phase A: scores of tile i+1 on the matrix pipe while the vector ALU turns the scores of tile i
-    //                   into bf16 probabilities; its last slices read the first V fragments of tile i
+    // Step i:  phase A: scores of tile i+1 on the matrix pipe while the vector ALU turns the scores of tile i
+    //                   into bf16 probabilities; its last slices read the first V fragments of tile i; then the
+    //                   check of the tile's sum and, rarely, the repair
     //          wait for K(i+2)'s copy, barrier (now the K buffer just read may be refilled with K(i+3), in phase B)
-    //          phase B: O^T += V^T P^T on the matrix pipe while the vector ALU reduces the running max of the
-    //                   new scores (masked first if tile i+1 needs it); its last slices read the first K fragments
-    //                   of tile i+2
+    //          phase B: O^T += V^T P^T on the matrix pipe while the vector ALU converts the first scores of tile
+    //                   i+1 (masked first if that tile needs it); its last slices read the first K fragments of
+    //                   tile i+2
     //          wait for V(i+1)'s copy, barrier (now the V buffer just read may be refilled, in the next phase A)
     // Each wait leaves the youngest copy in flight (IPW operations); near the end of the range, where that copy does
     // not exist, it waits for everything.  A tile is thus published one barrier before the phase that consumes it,
@@ -480,46 +483,35 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     // pipe does not idle for an LDS round trip after every barrier.
     bf16x8 kpre[4], vpre[4];
 
-    // matrix instruction idx (0..NQK-1) of a tile's scores for row block rb: the first of each chain starts from m_vec
+    // matrix instruction idx (0..NQK-1) of a tile's scores for row block rb: the first of each chain starts from zero
     auto score_mfma = [&](floatx16 &acc, const bf16x8 &kfrag, int rb, int idx) __attribute__((always_inline)) {
         if (ASM_MFMA) {
-            if (idx < 2) mfma_v_init(acc, kfrag, qf[rb][idx >> 1], m_vec[rb]);
+            if (idx < 2) mfma_v_init(acc, kfrag, qf[rb][idx >> 1]);
             else mfma_v_acc(acc, kfrag, qf[rb][idx >> 1]);
         } else {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[rb][idx >> 1], idx < 2 ? m_vec[rb] : acc, 0, 0, 0);
+            floatx16 zero;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) zero[j] = 0.f;
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag, qf[rb][idx >> 1], idx < 2 ? zero : acc, 0, 0, 0);
         }
     };
-    auto rescale = [&]() __attribute__((always_inline)) {
-        if (ASM_MFMA && (need_rescale[0] || need_rescale[RBW - 1])) mfma_settle();
-#pragma unroll
-        for (int rb = 0; rb < RBW; ++rb)
-            if (need_rescale[rb]) {
-#pragma unroll
-                for (int x = 0; x < MBD; ++x) {
-                    // take the value from the accumulator file and hand the product back to it inside the branch, or
-                    // the copies out of and into that file are hoisted in front of the branch and run on every step
-                    if (ASM_MFMA) asm volatile("" : "+a"(acc_o[rb][x]));
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) acc_o[rb][x][j] *= alpha[rb];
-                    if (ASM_MFMA) asm volatile("" : "+a"(acc_o[rb][x]));
-                }
-            }
-    };
-    // scores e and e+1 of `sc` (already shifted exponents of 2) -> bf16 probabilities, stored in accumulator-register
-    // order, and added to the lane's running sum.  Plain v_add_f32 on purpose: measured on this chip, ordinary vector
+    // raw scores e and e+1 of `sc` -> bf16 probabilities 2^(score*scale*log2(e) - offset), stored in accumulator-
+    // register order, and added to the lane's sum.  Plain v_add_f32 on purpose: measured on this chip, ordinary vector
     // instructions (add, fma, max3, cvt_pk_bf16) issue in the shadow of a running matrix instruction for free and
     // v_exp_f32 for three quarters, but v_dot2c_f32_bf16 (one instruction per pair) runs on the matrix pipe itself,
     // takes ~2.5x as long as an add and overlaps with nothing.
-    auto convert_pair = [&](floatx16 (&sc)[2], int e, float &sum, int rb) __attribute__((always_inline)) {
+    auto convert_pair_with = [&](floatx16 (&sc)[2], int e, float &sum, int rb, float minus_offset) __attribute__((always_inline)) {
         floatx2 x;
-        x[0] = __builtin_amdgcn_exp2f(sc[e / 16][e % 16]);
-        x[1] = __builtin_amdgcn_exp2f(sc[(e + 1) / 16][(e + 1) % 16]);
+        x[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e / 16][e % 16], c_log2, minus_offset));
+        x[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[(e + 1) / 16][(e + 1) % 16], c_log2, minus_offset));
         const bf16x2 pr = __builtin_convertvector(x, bf16x2);
         pf[rb][e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, pr);
         sum += x[0] + x[1];
         asm volatile("" : "+v"(sum));      // keeps the two additions in this slice (they would be collected behind the last one)
     };
-
+    auto convert_pair = [&](floatx16 (&sc)[2], int e, float &sum, int rb) __attribute__((always_inline)) {
+        convert_pair_with(sc, e, sum, rb, nm[rb]);
+    };
     // The exponentials are the vector ALU's heaviest load, so they are split between the two phases: phase B of
     // step i-1 converts scores 0..B_SCORES-1 of tile i (right after it has found the tile's max), phase A of step i
     // converts the rest.  A slice is one K or V fragment's worth of matrix instructions (one per row block).
@@ -570,29 +562,63 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         }
         // keep the conversions in this phase: without a use here the compiler sinks them next to their first use in
         // phase B, behind the barrier, and the overlap with the matrix pipe is lost
+        float tot[RBW];
+        bool trip = false;
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
             asm volatile("" : "+v"(pf[rb][1]), "+v"(pf[rb][2]), "+v"(pf[rb][3]), "+v"(sum[rb]));
             if (HAS_NEXT) asm volatile("" : "+v"(s_next[rb][0]), "+v"(s_next[rb][1]));
-            l_run[rb] += sum[rb];
+            tot[rb] = sum_carry[rb] + sum[rb];
+            trip |= !(tot[rb] < kSumRaise);         // also true for a sum that is not a number
+        }
+        if (__builtin_expect(__any(trip), 0)) {     // rare, wave-uniform, scalars only
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) adjust(tot[rb], rb);
+            pend_next = true;
+        } else {
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) l_run[rb] += tot[rb];
         }
     };
 
     // phase B.  vbuf: V buffer of the current tile.  HAS_NEXT: meanwhile the vector ALU masks s_next if `next_tile`
-    // is not a full prefix tile, reduces its max (first quarter of the slices), updates the running max and the
-    // running sum, and converts scores 0..15 (later slices; pf[0] and pf[1] have been consumed by then).
+    // is not a full prefix tile and converts its scores 0..B_SCORES-1 (from the slice at which pf[0], then pf[1], have
+    // been consumed), leaving their sum in sum_carry.
     // COPY_K spreads the copy of tile `k_tile` into K buffer `k_buf` over the slices.
     auto phase_b = [&](auto has_next_tag, auto copy_k_tag, auto full_tag, int vbuf, floatx16 (&s_next)[RBW][2], int next_tile, int k_tile, int k_buf, bool k_ahead, int k_next_buf) __attribute__((always_inline)) {
         constexpr bool COPY_K = decltype(copy_k_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
-        constexpr int MAX_SLICES = NPV / 4;             // slices that reduce the max
-        constexpr int MAX_PER_SLICE = 16 / MAX_SLICES;  // max3 operations (pairs of scores) per row block in each of them
-        constexpr int CONV_FIRST = MAX_SLICES + 2;      // first slice that converts (decision and fix-up come before)
+        constexpr int CONV_FIRST = MBD;                 // first slice that converts: pf[.][0] is last read by slice MBD-1
         constexpr int PAIRS = B_SCORES / 2 * RBW;       // pair q goes into slice CONV_FIRST + q*(NPV - CONV_FIRST)/PAIRS
-        // pf[.][0] is last read by slice MBD-1 and pf[.][1] by slice 2*MBD-1; they may be rewritten only after that
-        static_assert(CONV_FIRST >= MBD && (B_SCORES <= 8 || CONV_FIRST + ((4 * RBW) * (NPV - CONV_FIRST)) / PAIRS >= 2 * MBD),
+        // pf[.][1] is last read by slice 2*MBD-1 and may be rewritten only after that
+        static_assert(B_SCORES <= 8 || CONV_FIRST + ((4 * RBW) * (NPV - CONV_FIRST)) / PAIRS >= 2 * MBD,
                       "probabilities of the current tile would be overwritten before they are used");
+        if (__builtin_expect(pend_now | pend_next, 0)) {    // an offset moved one or two tiles ago
+            if (pend_now) {
+                if (ASM_MFMA) mfma_settle();
+#pragma unroll
+                for (int rb = 0; rb < RBW; ++rb) {
+#pragma unroll
+                    for (int x = 0; x < MBD; ++x) {
+                        // take the value from the accumulator file and hand the product back to it inside the branch,
+                        // or the copies out of and into that file are hoisted in front of the branch and run every step
+                        if (ASM_MFMA) asm volatile("" : "+a"(acc_o[rb][x]));
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) acc_o[rb][x][j] *= alpha_now[rb];
+                        if (ASM_MFMA) asm volatile("" : "+a"(acc_o[rb][x]));
+                    }
+                }
+                if (ASM_MFMA) mfma_settle();
+            }
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) {
+                alpha_now[rb] = alpha_next[rb];
+                alpha_next[rb] = 1.f;
+            }
+            pend_now = pend_next;
+            pend_next = false;
+        }
         bf16x8 vf[NPV];
 #pragma unroll
         for (int x = 0; x < 4; ++x) vf[x] = vpre[x];
@@ -601,13 +627,9 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
 #pragma unroll
             for (int rb = 0; rb < RBW; ++rb) apply_mask(s_next[rb], next_tile, rb);
         }
-        float mx0[RBW], mx1[RBW], sum[RBW];
+        float sum[RBW];
 #pragma unroll
-        for (int rb = 0; rb < RBW; ++rb) {
-            mx0[rb] = -__builtin_inff();
-            mx1[rb] = -__builtin_inff();
-            sum[rb] = 0.f;
-        }
+        for (int rb = 0; rb < RBW; ++rb) sum[rb] = 0.f;
         GSD_SLICE_END();
 #pragma unroll
         for (int idx = 0; idx < NPV; ++idx) {
@@ -625,16 +647,6 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                     }
                 }
                 if (HAS_NEXT) {
-                    if (idx < MAX_SLICES) {
-#pragma unroll
-                        for (int x = 0; x < MAX_PER_SLICE; ++x) {
-                            const int e = 2 * (idx * MAX_PER_SLICE + x);
-                            if (x & 1) mx1[rb] = max3(mx1[rb], s_next[rb][e / 16][e % 16], s_next[rb][(e + 1) / 16][(e + 1) % 16]);
-                            else mx0[rb] = max3(mx0[rb], s_next[rb][e / 16][e % 16], s_next[rb][(e + 1) / 16][(e + 1) % 16]);
-                        }
-                    }
-                    if (idx == MAX_SLICES) decide_max(fmaxf(mx0[rb], mx1[rb]), rb);
-                    if (idx == MAX_SLICES + 1) apply_max(s_next[rb], rb);
 #pragma unroll
                     for (int q = 0; q < PAIRS; ++q)
                         if (CONV_FIRST + (q * (NPV - CONV_FIRST)) / PAIRS == idx && q % RBW == rb)
@@ -647,7 +659,7 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
 #pragma unroll
             for (int rb = 0; rb < RBW; ++rb) {
                 asm volatile("" : "+v"(pf[rb][0]), "+v"(pf[rb][1]), "+v"(sum[rb]));
-                l_run[rb] += sum[rb];
+                sum_carry[rb] = sum[rb];
             }
         }
     };
@@ -676,17 +688,11 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 score_mfma(sa[rb][idx & 1], k_frag(0, idx), rb, idx);
             if (ASM_MFMA) mfma_settle();
             if (c0 >= full_end) apply_mask(sa[rb], c0, rb);
-            float mx = sa[rb][0][0];
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sa[rb][mb][j]);
-            decide_max(mx, rb);
-            apply_max(sa[rb], rb);
+            first_offset(sa[rb], rb);
             float sum = 0.f;
 #pragma unroll
             for (int e = 0; e < B_SCORES; e += 2) convert_pair(sa[rb], e, sum, rb);
-            l_run[rb] += sum;
+            sum_carry[rb] = sum;
         }
         wg_barrier();          // K buffer 0 has been read by every wave
         if (c2 < t_end) {
@@ -708,7 +714,6 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         auto step = [&](auto steady_tag, auto fast_tag, floatx16 (&cur)[RBW][2], floatx16 (&nxt)[RBW][2]) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;
             constexpr bool FAST = decltype(fast_tag)::value;
-            rescale();
             phase_a(True{}, fast_tag, (i + 1) & 1, cur, nxt, c1, (i + 1) & 1, i & 1);   // also starts the copy of V(i+1)
             if (STEADY) dma_wait<IPW>(); else dma_wait<0>();             // K(i+2) has landed (V(i) did a barrier ago)
             wg_barrier();
@@ -740,7 +745,6 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 for (int mb = 0; mb < 2; ++mb) sa[rb][mb] = sb[rb][mb];
         }
         // last tile: nothing left to prefetch or to score
-        rescale();
         phase_a(False{}, False{}, 0, sa, sb, 0, 0, i & 1);
         phase_b(False{}, False{}, False{}, i & 1, sb, 0, 0, 0, false, 0);
     }
@@ -748,14 +752,30 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     // ---- epilogue ------------------------------------------------------------------------------------------
     // accumulator register i of channel block mbd is channel  mbd*32 + 8*(i/4) + 4*half + i%4
     if (ASM_MFMA) mfma_settle();
+    uint32_t redo[RBW];        // wave-uniform: bit r = row r of row block rb goes through the exact path
 #pragma unroll
     for (int rb = 0; rb < RBW; ++rb) {
         const float l_tot = l_run[rb] + __shfl_xor(l_run[rb], 32, 64);
-        if (!row_is_valid(rb)) continue;
+        // A row total that is tiny (or zero, or not a number) although the row sees a key of this KV range means the
+        // offset sat far above every score: what was flushed to zero on the way may have mattered.
+        bool flagged = poison[rb];
+        if (!(l_tot >= kSumTiny)) {
+            bool sees = t_begin < min(t_end, ntp);
+#pragma unroll
+            for (int j = 0; j < kMaxWords; ++j)
+                sees |= j + ntp >= t_begin && j + ntp < t_end && my_mask[rb * 32 * kMaxWords + j] != 0;
+            flagged |= sees;
+        }
+        const bool valid = row_is_valid(rb);
+        const uint64_t votes = __ballot(flagged && valid);
+        redo[rb] = uint32_t(votes) | uint32_t(votes >> 32);
+        if (!valid || flagged) continue;
         const int64_t t = int64_t(node_base) + node_of(rb);
         const int32_t head = head_of(rb);
+        // a factor may still be parked for the accumulators (the last tile's sum tripped, or the one before it)
+        const float parked = alpha_now[rb] * alpha_next[rb];
         if (p.splits == 1) {
-            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            const float inv = l_tot > 0.f ? parked / l_tot : 0.f;
             __bf16 *op = p.o + t * p.o_ts + int64_t(head) * p.o_hs + 4 * half;
 #pragma unroll
             for (int mbd = 0; mbd < MBD; ++mbd)
@@ -768,7 +788,7 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 }
             if (p.lse && half == 0)
                 p.lse[t * p.num_q_heads + head] =
-                    l_tot > 0.f ? (m_run[rb] + __log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
+                    l_tot > 0.f ? (-nm[rb] + __log2f(l_tot)) * 0.6931471805599453f : -__builtin_inff();
         } else {
             const int64_t prow = (int64_t(split) * p.total_nodes + t) * p.num_q_heads + head;
             float *op = p.part_o + prow * D + 4 * half;
@@ -778,14 +798,111 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 for (int i4 = 0; i4 < 4; ++i4) {
                     floatx4 x;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] = acc_o[rb][mbd][i4 * 4 + e];
+                    for (int e = 0; e < 4; ++e) x[e] = acc_o[rb][mbd][i4 * 4 + e] * parked;
                     *reinterpret_cast<floatx4 *>(op + mbd * 32 + i4 * 8) = x;
                 }
             if (half == 0) {
                 floatx2 ml;
-                ml[0] = l_tot > 0.f ? m_run[rb] : kMInit;
+                ml[0] = l_tot > 0.f ? -nm[rb] : kMInit;
                 ml[1] = l_tot;
                 *reinterpret_cast<floatx2 *>(p.part_ml + prow * 2) = ml;
+            }
+        }
+    }
+
+    // ---- exact path for flagged rows (rare; correctness, not speed) ---------------------------------------------
+    // One row at a time, the whole wave on it: scores of up to kExactKeys keys at once, one key per lane, fp32 dot
+    // products against the query row parked in LDS; then one channel pair per lane walks those keys with a true
+    // running max.  Uses the K/V tile buffers, which every wave has finished with after the barrier.
+    bool any_redo = false;
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) any_redo |= redo[rb] != 0;
+    wg_barrier();
+    if (__builtin_expect(!any_redo, 1)) return;
+    constexpr int kExactKeys = 512;
+    constexpr int PER = D / 64;                    // output channels per lane
+    static_assert(L::kTotal / NW >= int((D + kExactKeys) * sizeof(float)), "per-wave share of the tile buffers");
+    float *q_lds = reinterpret_cast<float *>(lds + wave * (L::kTotal / NW));
+    float *s_lds = q_lds + D;
+    const int32_t pk0 = min(P, t_begin * kKeysPerTile), pk1 = min(P, t_end * kKeysPerTile);
+    const int32_t dn0 = min(n, max(t_begin - ntp, 0) * kKeysPerTile), dn1 = min(n, max(t_end - ntp, 0) * kKeysPerTile);
+    const int32_t n_prefix = pk1 - pk0, n_keys = n_prefix + (dn1 - dn0);
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+        for (uint32_t todo = redo[rb]; todo != 0; todo &= todo - 1) {
+            const int r = __builtin_ctz(todo);
+            const int32_t row = row0 + (wave * RBW + rb) * 32 + r;
+            const int32_t node = row / G, head = kvh * G + (row - node * G);
+            const int64_t t = int64_t(node_base) + node;
+            const uint64_t *mw = mask_lds + (wave * RBW * 32 + rb * 32 + r) * kMaxWords;
+            const __bf16 *qp = p.q + t * p.q_ts + int64_t(head) * p.q_hs;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the row before has been read out of LDS
+            for (int d = lane; d < D; d += 64) q_lds[d] = (float)qp[d];
+            float m = -__builtin_inff(), l = 0.f, o[PER];
+#pragma unroll
+            for (int e = 0; e < PER; ++e) o[e] = 0.f;
+            // key x of the range: prefix position pk0 + x, then draft node dn0 + (x - n_prefix)
+            auto kv_row = [&](int32_t x) -> int32_t { return x < n_prefix ? pk0 + x : P + dn0 + (x - n_prefix); };
+            auto visible = [&](int32_t x) -> bool {
+                if (x < n_prefix) return true;
+                const int32_t nd = dn0 + (x - n_prefix);
+                return (mw[nd >> 6] >> (nd & 63)) & 1;
+            };
+            for (int32_t base = 0; base < n_keys; base += kExactKeys) {
+                const int32_t cnt = min(kExactKeys, n_keys - base);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // q_lds written, s_lds of the chunk before read
+                float cmax = -__builtin_inff();
+                for (int32_t j = lane; j < cnt; j += 64) {
+                    float sc = -__builtin_inff();
+                    if (visible(base + j)) {
+                        const __bf16 *kp = k_seq + int64_t(kv_row(base + j)) * p.kv_ts;
+                        float dot = 0.f;
+                        for (int d = 0; d < D; d += 8) {
+                            const bf16x8 kk = *reinterpret_cast<const bf16x8 *>(kp + d);
+#pragma unroll
+                            for (int z = 0; z < 8; ++z) dot = __builtin_fmaf((float)kk[z], q_lds[d + z], dot);
+                        }
+                        sc = dot * c_log2;
+                    }
+                    s_lds[j] = sc;
+                    cmax = fmaxf(cmax, sc);
+                }
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, off, 64));
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the chunk's scores are in LDS
+                if (!(cmax > -__builtin_inff())) continue;          // nothing visible in this chunk
+                const float m_new = fmaxf(m, cmax);
+                const float shrink = m > -__builtin_inff() ? __builtin_amdgcn_exp2f(m - m_new) : 0.f;
+                m = m_new;
+                l *= shrink;
+#pragma unroll
+                for (int e = 0; e < PER; ++e) o[e] *= shrink;
+                for (int32_t j = 0; j < cnt; ++j) {
+                    const float sc = s_lds[j];                      // the same address in every lane
+                    if (!(sc > -__builtin_inff())) continue;
+                    const float pj = __builtin_amdgcn_exp2f(sc - m);
+                    l += pj;
+                    const __bf16 *vp = v_seq + int64_t(kv_row(base + j)) * p.kv_ts + lane * PER;
+#pragma unroll
+                    for (int e = 0; e < PER; ++e) o[e] = __builtin_fmaf(pj, (float)vp[e], o[e]);
+                }
+            }
+            if (p.splits == 1) {
+                const float inv = l > 0.f ? 1.f / l : 0.f;
+                __bf16 *op = p.o + t * p.o_ts + int64_t(head) * p.o_hs + lane * PER;
+#pragma unroll
+                for (int e = 0; e < PER; ++e) op[e] = (__bf16)(o[e] * inv);
+                if (p.lse && lane == 0)
+                    p.lse[t * p.num_q_heads + head] =
+                        l > 0.f ? (m + __log2f(l)) * 0.6931471805599453f : -__builtin_inff();
+            } else {
+                const int64_t prow = (int64_t(split) * p.total_nodes + t) * p.num_q_heads + head;
+#pragma unroll
+                for (int e = 0; e < PER; ++e) p.part_o[prow * D + lane * PER + e] = o[e];
+                if (lane == 0) {
+                    p.part_ml[prow * 2] = l > 0.f ? m : kMInit;
+                    p.part_ml[prow * 2 + 1] = l;
+                }
             }
         }
     }
@@ -896,7 +1013,6 @@ hipError_t launch_attention_bf16(const gsd_attn_desc &d, int splits, hipStream_t
     p.q_tiles = q_tiles_of(d);
     p.splits = splits;
     p.wg_per_xcd = (d.batch * d.num_kv_heads + 7) / 8 * p.q_tiles * splits;
-    p.scale = d.softmax_scale;
     p.scale_log2e = d.softmax_scale * kLog2e;
 
     const WgShape sh = shape_of(d);
