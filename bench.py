@@ -218,6 +218,29 @@ def bench_unmerge(gsd, w, dev, stream, reps=20):
             "attention_cost_ratio_tree_over_graph": {"flops": tree_flops / dag_flops, "time": tree_ms / dag_ms}}
 
 
+_bench_lib = None
+
+
+def mfma_loop(operands, work_groups: int, iters: int, sink=None):
+    """The bare matrix-instruction loop of libgsd_bench.so (csrc/bench_mfma_loop.hip) on torch's current stream."""
+    import ctypes
+    import torch
+    import paper_2407_16207_amd as gsd
+    from paper_2407_16207_amd.build import BENCH_LIB_PATH
+    global _bench_lib
+    if _bench_lib is None:
+        gsd.load_library()                      # makes torch's HIP runtime visible first
+        _bench_lib = ctypes.CDLL(BENCH_LIB_PATH)
+        _bench_lib.gsd_bench_mfma_loop.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                   ctypes.c_void_p, ctypes.c_void_p]
+    if sink is None:
+        sink = torch.empty(work_groups * 512, dtype=torch.float32, device=operands.device)
+    rc = _bench_lib.gsd_bench_mfma_loop(operands.data_ptr(), operands.numel() * operands.element_size(), work_groups,
+                                        iters, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert rc == 0, rc
+    return sink
+
+
 def bench_matrix_pipe(gsd, w, q, k, v, kv_offsets, prefix_lens, node_offsets, mask, out, workspace, need, flops,
                       stream, splits, reps=20):
     """What the chip's matrix pipe sustains for these operand statistics, next to the attention kernel: a bare loop
@@ -235,7 +258,7 @@ def bench_matrix_pipe(gsd, w, q, k, v, kv_offsets, prefix_lens, node_offsets, ma
     for name, operands in (("zeros", torch.zeros(wgs * 512 * 16 * 8, dtype=torch.bfloat16, device="cuda")),
                            ("normal", torch.randn(wgs * 512 * 16 * 8, generator=g, device="cuda",
                                                   dtype=torch.float32).to(torch.bfloat16))):
-        ms = time_launches(stream, lambda i: gsd.gsd_diag_mfma_loop(operands, wgs, iters, sink=sink), 6, warmup=3)
+        ms = time_launches(stream, lambda i: mfma_loop(operands, wgs, iters, sink=sink), 6, warmup=3)
         res["bare_mfma_loop_tflops_" + name] = loop_flops / ms / 1e9
     qz, kz, vz = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
     dz = gsd.make_attn_desc(qz, kz, vz, kv_offsets, prefix_lens, node_offsets, mask, w.max_nodes,

@@ -10,7 +10,7 @@
  *   gsd_accept_longest_path   longest root path on which every drafted token equals the verifier's choice
  * and, around that pass,
  *   gsd_unmerge_to_tree       token graph -> token tree with replicated successors (Section 5.4), gsd_gather_rows
- *   gsd_commit_kv             accepted path -> contiguous context rows of the KV cache (Section 6.5)
+ *   gsd_commit_kv             accepted path -> contiguous context rows of the KV cache (Section 7.1)
  *   gsd_accept_stochastic     non-deterministic verification (Sections 3, 6.4), gsd_softmax_stats
  *   gsd_build_token_graph     drafted token tree -> pruned, merged token graph (Sections 4.2, 5.2, 5.3)
  *
@@ -23,7 +23,8 @@
  *     unsupported head_dim, head counts that do not divide, words_per_row or workspace too small) are
  *     reported before anything is launched and leave all outputs untouched; gsd_last_error() then holds a
  *     detail string for the calling thread.  Mistakes only the device can see (a parent id that is not an
- *     earlier node) are reported through `dag_error_flag`.
+ *     earlier node, i.e. a graph that is not listed in topological order) are reported through `dag_error_flag`,
+ *     never through the return value: the library does not wait for the device.
  *   - Packed nodes: sequence b owns packed rows node_offsets[b] .. node_offsets[b+1]-1, listed in a
  *     topological order of its graph; parent ids are sequence-local, -1 names the root (the context at the
  *     start of drafting, Section 4).
@@ -41,7 +42,6 @@ extern "C" {
 enum {
     GSD_OK = 0,
     GSD_ERR_INVALID_ARG = 1,
-    GSD_ERR_NOT_TOPOLOGICAL = 2, /* reserved for callers that read dag_error_flag back */
     GSD_ERR_UNSUPPORTED = 3,
     GSD_ERR_WORKSPACE = 4,
     GSD_ERR_HIP = 5
@@ -207,7 +207,7 @@ int gsd_gather_rows(int64_t rows, int64_t row_bytes, const void *src, int64_t sr
                     const int32_t *index, void *dst, int64_t dst_stride_bytes, void *hip_stream);
 
 /*
- * KV-cache commit after acceptance (Section 6.5 finds the cache update to be a cost of its own next to drafting
+ * KV-cache commit after acceptance (Section 7.1 finds the cache update to be a cost of its own next to drafting
  * and verifying).  The accepted draft tokens become context, everything else drafted in this iteration is
  * dropped: for every layer l, for K and for V, and every j < accept_len[b]
  *     row (kv_offsets[b] + P_b + j)  <-  row (kv_offsets[b] + P_b + accept_path[b][j])        (P_b = prefix_lens[b])

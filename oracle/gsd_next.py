@@ -1,5 +1,5 @@
 """CPU oracle of the steps around the verify pass: un-merging the token graph into a token tree (Section 5.4),
-committing the accepted path to the KV cache (the cache update of Section 6.5) and non-deterministic verification
+committing the accepted path to the KV cache (the cache update of Section 7.1) and non-deterministic verification
 (Sections 3 and 6.4).  TEST INFRASTRUCTURE ONLY.
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module; the product path never
@@ -67,7 +67,7 @@ def unmerge_to_tree(node_offsets, parent_offsets, parent_idx, max_tree_nodes):
 
 
 def commit_kv(k, v, kv_offsets, prefix_lens, accept_len, accept_path):
-    """Cache update after acceptance (Section 6.5 attributes the "Others" time to it): the accepted tokens become
+    """Cache update after acceptance (Section 7.1 attributes the "Others" time to it): the accepted tokens become
     part of the context, everything else drafted in this iteration is dropped.  With a sequence's rows laid out
     as [prefix rows ; draft rows], the new context of sequence b is
         old prefix rows, then the rows of accept_path[b][0 .. accept_len[b]) in path order.

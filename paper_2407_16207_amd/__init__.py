@@ -17,14 +17,14 @@ _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libgsd.so")
 
 GSD_OK = 0
-GSD_ERR_INVALID_ARG, GSD_ERR_NOT_TOPOLOGICAL, GSD_ERR_UNSUPPORTED, GSD_ERR_WORKSPACE, GSD_ERR_HIP = 1, 2, 3, 4, 5
+GSD_ERR_INVALID_ARG, GSD_ERR_UNSUPPORTED, GSD_ERR_WORKSPACE, GSD_ERR_HIP = 1, 3, 4, 5
 GSD_F32, GSD_BF16 = 0, 1
 GSD_MAX_NODES_PER_SEQ = 512
 
 EXPORTS = ("gsd_status_string", "gsd_last_error", "gsd_version", "gsd_build_mask", "gsd_dag_attention_workspace",
            "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_node_argmax", "gsd_accept_longest_path",
            "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv", "gsd_softmax_stats", "gsd_accept_stochastic",
-           "gsd_build_token_graph", "gsd_diag_mfma_loop")
+           "gsd_build_token_graph")
 
 
 class GsdError(RuntimeError):
@@ -107,7 +107,6 @@ def load_library() -> ctypes.CDLL:
         lib.gsd_accept_stochastic.argtypes = [ctypes.POINTER(StochasticDesc), vp]
         lib.gsd_build_token_graph.argtypes = [i32, i32, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp, vp, vp, vp,
                                               vp, i64, vp, vp, vp, vp]
-        lib.gsd_diag_mfma_loop.argtypes = [vp, i64, i32, i32, vp, vp]
         _lib = lib
     return _lib
 
@@ -446,19 +445,3 @@ def gsd_build_token_graph(node_offsets, tree_parent, tokens, draft_prob, max_nod
                                                 _ptr(g_off), _ptr(p_off), _ptr(p_idx), cap, _ptr(origin), _ptr(flags),
                                                 _ptr(error_flag), _stream_ptr(stream)))
     return g_off, p_off, p_idx, origin, flags, counts
-
-
-def gsd_diag_mfma_loop(operands, work_groups: int, iters: int, sink=None, stream=None):
-    """Measurement aid: a bare loop of the attention kernel's matrix instruction fed from `operands` (any GPU tensor,
-    taken as raw 16-byte fragments).  Returns the sink tensor.  See gsd_diag_mfma_loop in gsd_diag.h."""
-    import torch
-    if not operands.is_cuda or not operands.is_contiguous():
-        raise ValueError("operands must be a contiguous GPU tensor")
-    nbytes = operands.numel() * operands.element_size()
-    sink = torch.empty(work_groups * 512, dtype=torch.float32, device=operands.device) if sink is None else sink
-    _require(sink, torch.float32, "sink")
-    if sink.numel() < work_groups * 512:
-        raise ValueError("sink too small")
-    _check(load_library().gsd_diag_mfma_loop(_ptr(operands), nbytes, work_groups, iters, _ptr(sink),
-                                             _stream_ptr(stream)))
-    return sink

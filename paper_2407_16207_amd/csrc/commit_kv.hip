@@ -1,4 +1,4 @@
-// KV-cache commit of the accepted path (paper Section 6.5: the cache update is a cost of its own).
+// KV-cache commit of the accepted path (paper Section 7.1: the cache update is a cost of its own).
 //
 // Per sequence, layer and K|V the accepted draft rows are compacted in place behind the prefix:
 //     row P+j <- row P+path[j],  j = 0 .. accept_len-1,  path strictly increasing so path[j] >= j.

@@ -5,7 +5,6 @@
 #include <cstring>
 
 #include "gsd_internal.h"
-#include "gsd_diag.h"
 
 namespace {
 
@@ -56,7 +55,6 @@ const char *gsd_status_string(int status) {
     switch (status) {
         case GSD_OK: return "ok";
         case GSD_ERR_INVALID_ARG: return "invalid argument";
-        case GSD_ERR_NOT_TOPOLOGICAL: return "graph is not in topological order";
         case GSD_ERR_UNSUPPORTED: return "unsupported configuration";
         case GSD_ERR_WORKSPACE: return "workspace too small";
         case GSD_ERR_HIP: return "HIP runtime error";
@@ -76,8 +74,6 @@ int gsd_build_mask(int32_t batch, int32_t max_nodes, int32_t words_per_row, cons
         return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", max_nodes, GSD_MAX_NODES_PER_SEQ);
     if (words_per_row < (max_nodes + 63) / 64)
         return fail(GSD_ERR_INVALID_ARG, "words_per_row %d too small for max_nodes %d", words_per_row, max_nodes);
-    if (size_t(max_nodes) * words_per_row * sizeof(uint64_t) > 32768)
-        return fail(GSD_ERR_UNSUPPORTED, "max_nodes * words_per_row exceeds 4096 words");
     if (!node_offsets || !parent_offsets || !parent_idx || !mask)
         return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
     hipError_t err = gsd::launch_build_mask(batch, max_nodes, words_per_row, node_offsets, parent_offsets,
@@ -283,19 +279,6 @@ int gsd_build_token_graph(int32_t batch, int32_t max_nodes, int32_t tau, float t
                                              parent_idx, edge_capacity, origin, flags, error_flag,
                                              (hipStream_t)hip_stream);
     return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_build_token_graph launch");
-}
-
-int gsd_diag_mfma_loop(const void *operands, int64_t operand_bytes, int32_t work_groups, int32_t iters, float *sink,
-                       void *hip_stream) {
-    if (!operands || !sink) return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
-    if (operand_bytes < 16 || operand_bytes % 16 != 0 || operand_bytes / 16 > INT64_C(0xffffffff))
-        return fail(GSD_ERR_INVALID_ARG, "operand_bytes %lld must be a positive multiple of 16", (long long)operand_bytes);
-    if (reinterpret_cast<uintptr_t>(operands) % 16 != 0) return fail(GSD_ERR_INVALID_ARG, "operands misaligned");
-    if (work_groups < 1 || work_groups > 65536 || iters < 1 || iters > (1 << 20))
-        return fail(GSD_ERR_INVALID_ARG, "work_groups %d or iters %d out of range", work_groups, iters);
-    hipError_t err = gsd::launch_diag_mfma_loop(operands, operand_bytes, work_groups, iters, sink,
-                                                (hipStream_t)hip_stream);
-    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_diag_mfma_loop launch");
 }
 
 }  // extern "C"

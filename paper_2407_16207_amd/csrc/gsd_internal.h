@@ -51,7 +51,4 @@ hipError_t launch_build_graph(int32_t batch, int32_t max_nodes, const int32_t *n
                               int32_t *parent_idx, int64_t edge_capacity, int32_t *origin, int32_t *flags,
                               int32_t *error_flag, hipStream_t stream);
 
-hipError_t launch_diag_mfma_loop(const void *operands, int64_t operand_bytes, int32_t work_groups, int32_t iters,
-                                 float *sink, hipStream_t stream);
-
 }  // namespace gsd

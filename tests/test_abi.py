@@ -160,16 +160,3 @@ def test_stochastic_entry_points_validate(lib):
         d = good()
         setattr(d, field, value)
         assert lib.gsd_accept_stochastic(ctypes.byref(d), null) == code, field
-
-
-def test_measurement_aid_validates(lib):
-    p = ctypes.c_void_p(0x10000)
-    null = ctypes.c_void_p(0)
-    assert lib.gsd_diag_mfma_loop(null, 1024, 4, 10, p, null) == gsd.GSD_ERR_INVALID_ARG
-    assert lib.gsd_diag_mfma_loop(p, 1024, 4, 10, null, null) == gsd.GSD_ERR_INVALID_ARG
-    assert lib.gsd_diag_mfma_loop(p, 1000, 4, 10, p, null) == gsd.GSD_ERR_INVALID_ARG       # not a multiple of 16
-    assert lib.gsd_diag_mfma_loop(p, 0, 4, 10, p, null) == gsd.GSD_ERR_INVALID_ARG
-    assert lib.gsd_diag_mfma_loop(ctypes.c_void_p(0x10008), 1024, 4, 10, p, null) == gsd.GSD_ERR_INVALID_ARG
-    assert lib.gsd_diag_mfma_loop(p, 1024, 0, 10, p, null) == gsd.GSD_ERR_INVALID_ARG
-    assert lib.gsd_diag_mfma_loop(p, 1024, 4, 0, p, null) == gsd.GSD_ERR_INVALID_ARG
-    assert lib.gsd_diag_mfma_loop(p, 1024, 1 << 20, 10, p, null) == gsd.GSD_ERR_INVALID_ARG

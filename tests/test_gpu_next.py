@@ -1,5 +1,5 @@
 """GPU parity for the steps around the verify pass: un-merge-to-tree (Section 5.4) and the KV-cache commit
-(Section 6.5), through the C ABI, bit-exact against the CPU oracle; and the tree variant of the whole verify
+(Section 7.1), through the C ABI, bit-exact against the CPU oracle; and the tree variant of the whole verify
 pass against the oracle run on the oracle's tree."""
 import numpy as np
 import pytest
@@ -410,12 +410,13 @@ def test_build_token_graph_flags_bad_input_and_small_capacity(gpu):
 
 
 def test_measurement_aid_counts_what_it_says(gpu):
-    """The bare matrix-instruction loop really issues iters*16 instructions per lane: with all-ones operands every
-    instruction adds 16 to each of a lane's 64 accumulator elements, four instructions per accumulator block and trip."""
-    import paper_2407_16207_amd as gsd
+    """The benchmark's bare matrix-instruction loop really issues iters*16 instructions per lane: with all-ones operands
+    every instruction adds 16 to each of a lane's 64 accumulator elements, four instructions per accumulator block and
+    trip."""
+    import bench
     ones = torch.ones(4096, dtype=torch.bfloat16, device="cuda")
     for wgs, iters in ((3, 1), (5, 7)):
-        sink = gsd.gsd_diag_mfma_loop(ones, wgs, iters)
+        sink = bench.mfma_loop(ones, wgs, iters)
         torch.cuda.synchronize()
         assert sink.numel() == wgs * 512
         assert torch.all(sink == 64.0 * 16.0 * 4 * iters)

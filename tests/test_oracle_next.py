@@ -1,4 +1,4 @@
-"""Pins for the oracle's un-merge-to-tree step (Section 5.4) and KV-cache commit (Section 6.5)."""
+"""Pins for the oracle's un-merge-to-tree step (Section 5.4) and KV-cache commit (Section 7.1)."""
 import numpy as np
 import pytest
 
