@@ -135,6 +135,19 @@ int gsd_dag_attention_splits(const gsd_attn_desc *desc);
 int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream);
 
 /*
+ * gsd_dag_attention for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the same results, but the
+ * split-KV partials live in an array of GSD_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until
+ * the process ends.  desc->workspace and desc->workspace_bytes are ignored.  A descriptor whose partials
+ * (gsd_dag_attention_workspace() bytes) exceed GSD_STATIC_SCRATCH_BYTES is rejected with GSD_ERR_WORKSPACE before
+ * anything is launched.  Calls no allocating routine.  All calls on one GPU share that GPU's array: two calls that
+ * overlap in time on one GPU (different streams, different threads) race and give wrong results; calls on one
+ * stream are safe.  Nothing in the array has to start at zero: a launch writes every partial it later reads.
+ */
+#define GSD_STATIC_SCRATCH_BYTES (32u << 20)
+int gsd_dag_attention_static(const gsd_attn_desc *desc, void *hip_stream);
+
+/*
  * Deterministic verification, part 1 (Section 3: a drafted token is accepted only if the LLM would generate
  * the same): pred[r] = the lowest index holding the largest value of row r of the logits.  NaN never wins; a
  * row of only NaN gives 0.  logits element (r, x) lives at r*row_stride + x (elements).

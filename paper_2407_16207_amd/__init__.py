@@ -20,9 +20,10 @@ GSD_OK = 0
 GSD_ERR_INVALID_ARG, GSD_ERR_UNSUPPORTED, GSD_ERR_WORKSPACE, GSD_ERR_HIP = 1, 3, 4, 5
 GSD_F32, GSD_BF16 = 0, 1
 GSD_MAX_NODES_PER_SEQ = 512
+GSD_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ("gsd_status_string", "gsd_last_error", "gsd_version", "gsd_build_mask", "gsd_dag_attention_workspace",
-           "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_node_argmax", "gsd_accept_longest_path",
+           "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_dag_attention_static", "gsd_node_argmax", "gsd_accept_longest_path",
            "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv", "gsd_softmax_stats", "gsd_accept_stochastic",
            "gsd_build_token_graph")
 
@@ -95,6 +96,7 @@ def load_library() -> ctypes.CDLL:
         lib.gsd_dag_attention_workspace.argtypes = [ctypes.POINTER(AttnDesc)]
         lib.gsd_dag_attention_splits.argtypes = [ctypes.POINTER(AttnDesc)]
         lib.gsd_dag_attention.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_void_p]
+        lib.gsd_dag_attention_static.argtypes = [ctypes.POINTER(AttnDesc), ctypes.c_void_p]
         i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
         lib.gsd_build_mask.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp]
         lib.gsd_node_argmax.argtypes = [i32, i32, ctypes.c_int, vp, i64, vp, vp]
@@ -242,6 +244,12 @@ def gsd_dag_attention(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, max_
 def gsd_dag_attention_desc(desc: AttnDesc, stream=None):
     """Launch from a prepared descriptor (no allocation, for timing loops)."""
     _check(load_library().gsd_dag_attention(ctypes.byref(desc), _stream_ptr(stream)))
+
+
+def gsd_dag_attention_static(desc: AttnDesc, stream=None):
+    """gsd_dag_attention_static of gsd.h: launch from a prepared descriptor, split partials in the library's static
+    scratch array (the descriptor's workspace fields are ignored).  Allocates nothing."""
+    _check(load_library().gsd_dag_attention_static(ctypes.byref(desc), _stream_ptr(stream)))
 
 
 def gsd_node_argmax(logits, pred=None, stream=None):

@@ -31,6 +31,7 @@
 //
 // Small problems are split along the KV axis (gsd_attn_desc.num_splits); a split writes unnormalised fp32
 // partials (O, running max, running sum) and a second kernel merges them in split order.
+#include <mutex>
 #include <type_traits>
 
 #include "gsd_internal.h"
@@ -997,6 +998,32 @@ int attention_bf16_splits(const gsd_attn_desc &d) {
 size_t attention_bf16_workspace(const gsd_attn_desc &d, int splits) {
     if (splits <= 1) return 0;
     return size_t(splits) * d.total_nodes * d.num_q_heads * (size_t(d.head_dim) + 2) * sizeof(float);
+}
+
+// Scratch of the allocation-free entry point (gsd_dag_attention_static): the split-KV partials live in this array
+// instead of a caller workspace.  Every GPU the library runs on holds its own copy at its own address until the
+// process ends.  In host code the array's name is only a handle for the runtime: the device address is asked for
+// once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[GSD_STATIC_SCRATCH_BYTES];
+
+hipError_t attention_static_scratch(void **ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void *address[kMaxDevices];           // zero-initialised: not asked yet
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!address[dev]) {
+        void *found = nullptr;
+        err = hipGetSymbolAddress(&found, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return err;
+        if (!found) return hipErrorInvalidSymbol;
+        address[dev] = found;
+    }
+    *ptr = address[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_attention_bf16(const gsd_attn_desc &d, int splits, hipStream_t stream) {

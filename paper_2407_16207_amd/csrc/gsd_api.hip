@@ -92,10 +92,12 @@ size_t gsd_dag_attention_workspace(const gsd_attn_desc *desc) {
     return gsd::attention_bf16_workspace(*desc, gsd::attention_bf16_splits(*desc));
 }
 
-int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream) {
-    int rc = check_attn_desc(desc);
-    if (rc != GSD_OK) return rc;
-    const gsd_attn_desc &d = *desc;
+}  // extern "C"
+
+namespace {
+
+// Shared by the two attention entry points: everything but where the split partials live.
+int check_attn_buffers(const gsd_attn_desc &d) {
     if (!d.q || !d.o || !d.k || !d.v || !d.kv_offsets || !d.prefix_lens || !d.node_offsets || !d.mask)
         return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
     const int64_t align = d.dtype == GSD_BF16 ? 8 : 4;
@@ -116,6 +118,19 @@ int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream) {
             (int64_t(d.max_prefix) + d.max_nodes) * row_bytes >= (int64_t(1) << 31))
             return fail(GSD_ERR_UNSUPPORTED, "one sequence's K/V rows span 2 GiB or more (or a row stride >= 16 MiB)");
     }
+    return GSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream) {
+    int rc = check_attn_desc(desc);
+    if (rc != GSD_OK) return rc;
+    const gsd_attn_desc &d = *desc;
+    rc = check_attn_buffers(d);
+    if (rc != GSD_OK) return rc;
     hipStream_t stream = (hipStream_t)hip_stream;
     hipError_t err;
     if (d.dtype == GSD_F32) {
@@ -130,6 +145,36 @@ int gsd_dag_attention(const gsd_attn_desc *desc, void *hip_stream) {
         err = gsd::launch_attention_bf16(d, splits, stream);
     }
     return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_dag_attention launch");
+}
+
+int gsd_dag_attention_static(const gsd_attn_desc *desc, void *hip_stream) {
+    int rc = check_attn_desc(desc);
+    if (rc != GSD_OK) return rc;
+    gsd_attn_desc d = *desc;
+    rc = check_attn_buffers(d);
+    if (rc != GSD_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    hipError_t err;
+    if (d.dtype == GSD_F32) {
+        err = gsd::launch_attention_f32(d, stream);
+    } else {
+        const int splits = gsd::attention_bf16_splits(d);
+        const size_t need = gsd::attention_bf16_workspace(d, splits);
+        if (need > GSD_STATIC_SCRATCH_BYTES)
+            return fail(GSD_ERR_WORKSPACE, "%zu bytes of split partials (%d KV splits) exceed the static scratch of %zu",
+                        need, splits, size_t(GSD_STATIC_SCRATCH_BYTES));
+        d.workspace = nullptr;
+        d.workspace_bytes = 0;
+        if (need > 0) {
+            void *ptr = nullptr;
+            err = gsd::attention_static_scratch(&ptr);
+            if (err != hipSuccess) return hip_fail(err, "gsd_dag_attention_static scratch address");
+            d.workspace = ptr;
+            d.workspace_bytes = GSD_STATIC_SCRATCH_BYTES;
+        }
+        err = gsd::launch_attention_bf16(d, splits, stream);
+    }
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_dag_attention_static launch");
 }
 
 int gsd_node_argmax(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,

@@ -26,6 +26,8 @@ hipError_t launch_attention_f32(const gsd_attn_desc &d, hipStream_t stream);
 int attention_bf16_splits(const gsd_attn_desc &d);
 size_t attention_bf16_workspace(const gsd_attn_desc &d, int splits);
 hipError_t launch_attention_bf16(const gsd_attn_desc &d, int splits, hipStream_t stream);
+// device address, on the current device, of the library's static scratch array of GSD_STATIC_SCRATCH_BYTES
+hipError_t attention_static_scratch(void **ptr);
 
 hipError_t launch_unmerge(int32_t batch, int32_t max_nodes, int32_t max_tree_nodes, const int32_t *node_offsets,
                           const int32_t *parent_offsets, const int32_t *parent_idx, int32_t *tree_node_offsets,
