@@ -188,19 +188,21 @@ def build_token_graph(node_offsets, tree_parent, tokens, draft_prob, tau, theta_
       * sibling pruning (Section 4.2): a node with draft_prob < theta_sib * (largest draft_prob among the children of
         its parent, itself included) becomes a leaf;
       * redundancy (Section 5.2): a node of depth >= tau whose tau-gram (its token and those of its tau-1 nearest
-        ancestors) equals the tau-gram of an EARLIER existing node is tau-redundant; the earliest such node is the
-        first occurrence F.  The redundant node R becomes a leaf (Section 5.3).  If F lies in the same layer as R its
-        children are still to be generated, and they are generated once for both: every child of F gets R as one
-        more parent (the merge edge).  If F lies in an earlier layer its children already exist above R; no edge is
-        drawn then (edges from a later layer back into an earlier one can close cycles, a case the paper does not
-        treat): R is a leaf all the same, which is where the saving comes from;
+        ancestors in the tree) equals the tau-gram of an EARLIER existing node is tau-redundant; the earliest such node
+        is the first occurrence F.  The redundant node R becomes a leaf (Section 5.3);
+      * merging (Section 5.3 draws an edge from R to F so that what follows F is reused below R): R becomes one more
+        parent of every child of F, wherever F lies (its children may be generated later, if F is in R's own layer,
+        or exist already, if F is in an earlier layer).  The one case the paper does not treat is an R that descends
+        from F in the graph built so far (all parent edges, merge edges included): reusing F's children below R would
+        close a cycle, so then no edge is drawn and R is only a leaf;
       * a node is expanded iff none of the three made it a leaf.
 
-    Existing nodes keep their generation order (it is a topological order of the graph: every edge goes from one
-    layer to the next).  Returns packed arrays
+    An edge from a later layer into an earlier one breaks the generation order as a topological order, so the graph is
+    renumbered: by level (0 for children of the root, else one more than the largest level among the parents), nodes
+    of one level in generation order.  Without such edges this is the generation order itself.  Returns packed arrays
         (graph_node_offsets[B+1], parent_offsets[T'+1], parent_idx[E] (new sequence-local ids, ascending, -1 = root),
          origin[T'] (tree id), flags[T'] bit0 = probability-pruned, bit1 = sibling-pruned, bit2 = redundant,
-         bit3 = redundant with its first occurrence in an earlier layer (no merge edge))."""
+         bit3 = redundant and a descendant of its first occurrence (no merge edge))."""
     node_offsets = np.asarray(node_offsets, dtype=np.int64)
     B = len(node_offsets) - 1
     g_off, p_off, p_idx, origin_all, flags_all = [0], [0], [], [], []
@@ -224,6 +226,22 @@ def build_token_graph(node_offsets, tree_parent, tokens, draft_prob, tau, theta_
             sib_max[par[i]] = max(sib_max.get(par[i], 0.0), q[i])
             depth[i] = 1 if par[i] == -1 else depth[par[i]] + 1
             assert i == 0 or depth[i] >= depth[i - 1], "nodes must come in breadth-first order"
+
+        def graph_parents(x):
+            """Parents of existing node x in the graph built so far: its tree parent and whatever merged into it."""
+            return [par[x]] + merged_into.get(par[x], [])
+
+        def descends_from(x, f):
+            seen, stack = set(), [x]
+            while stack:
+                for r in graph_parents(stack.pop()):
+                    if r == f:
+                        return True
+                    if r != -1 and r not in seen:
+                        seen.add(r)
+                        stack.append(r)
+            return False
+
         for i in range(n):
             p = par[i]
             if not (p == -1 or (exists[p] and expanded[p])):
@@ -243,18 +261,27 @@ def build_token_graph(node_offsets, tree_parent, tokens, draft_prob, tau, theta_
                 for j in range(i):
                     if exists[j] and gram[j] == gram[i]:
                         flags[i] |= 4
-                        if depth[j] == depth[i]:
-                            merged_into.setdefault(j, []).append(i)
-                        else:
+                        if descends_from(i, j):
                             flags[i] |= 8
+                        else:
+                            merged_into.setdefault(j, []).append(i)
                         break
             expanded[i] = flags[i] == 0
         kept = [i for i in range(n) if exists[i]]
-        new_id = {old: k for k, old in enumerate(kept)}
-        for old in kept:
-            ps = [par[old]] + merged_into.get(par[old], [])
-            ps = [-1 if r == -1 else new_id[r] for r in ps]
-            assert ps == sorted(ps) and all(r < new_id[old] for r in ps)
+        level = {}
+        for old in kept:                          # a parent that is a later node is a redundant leaf of a deeper layer,
+            level[old] = None                     # whose own parents are earlier nodes: resolve on demand
+
+        def level_of(x):
+            if level[x] is None:
+                level[x] = 0 if graph_parents(x) == [-1] else 1 + max(level_of(r) for r in graph_parents(x) if r != -1)
+            return level[x]
+
+        order = sorted(kept, key=lambda x: (level_of(x), x))
+        new_id = {old: k for k, old in enumerate(order)}
+        for old in order:
+            ps = sorted(-1 if r == -1 else new_id[r] for r in graph_parents(old))
+            assert all(r < new_id[old] for r in ps)
             p_idx.extend(ps)
             p_off.append(len(p_idx))
             origin_all.append(old)

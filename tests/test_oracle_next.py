@@ -374,10 +374,23 @@ def test_merged_graph_spells_exactly_the_hypotheses_of_the_definition(seed):
     kids = {}
     for i, p in enumerate(par):
         kids.setdefault(int(p), []).append(i)
-    gram_of, first_seen, exists, follows = {}, {}, set(), {}
-    dep = [0] * n
-    for i in range(n):
-        dep[i] = 1 if par[i] == -1 else dep[int(par[i])] + 1
+    first_seen, exists, follows = {}, set(), {}
+
+    def continuations(v):                                  # the nodes a hypothesis can go to after v, so far
+        src = follows.get(v)
+        return [] if src is None else [c for c in kids.get(src, []) if c in exists]
+
+    def hypothesis_passes(f, r):                           # some hypothesis built so far visits f and later r
+        seen, todo = {f}, [f]
+        while todo:
+            for c in continuations(todo.pop()):
+                if c == r:
+                    return True
+                if c not in seen:
+                    seen.add(c)
+                    todo.append(c)
+        return False
+
     for i in range(n):
         p = int(par[i])
         if p != -1 and (p not in exists or follows[p] != p):
@@ -391,7 +404,11 @@ def test_merged_graph_spells_exactly_the_hypotheses_of_the_definition(seed):
             key = tuple(g)
             if key in first_seen:
                 f = first_seen[key]
-                follows[i] = f if dep[f] == dep[i] else None     # leaf; continues with f's children if f is in its layer
+                # Section 5.3: a leaf that continues with whatever follows the first occurrence f, wherever f lies;
+                # unless the hypotheses through f already run into i (then reuse would loop: a leaf only)
+                follows[i] = None
+                if not hypothesis_passes(f, i):
+                    follows[i] = f
             else:
                 first_seen[key] = i
     want = set()
@@ -417,9 +434,19 @@ def test_merged_graph_spells_exactly_the_hypotheses_of_the_definition(seed):
             if len(g) == tau:
                 assert tuple(g) not in grams
                 grams[tuple(g)] = old
-    # numbering: parents first
+    # numbering: parents first; by level (longest distance from the root), nodes of one level in generation order
+    level = []
     for k in range(m):
-        assert all(r < k for r in p_idx[p_off[k]:p_off[k + 1]])
+        ps = [int(r) for r in p_idx[p_off[k]:p_off[k + 1]]]
+        assert all(r < k for r in ps) and ps == sorted(ps)
+        level.append(0 if ps == [-1] else 1 + max(level[r] for r in ps if r != -1))
+    keys = [(level[k], int(origin[k])) for k in range(m)]
+    assert keys == sorted(keys)
+    # a redundant node is a leaf; bit 3 marks exactly those whose first occurrence leads to them
+    for k, old in enumerate(origin):
+        if flags[k] & 4:
+            assert follows[int(old)] != int(old)
+            assert bool(flags[k] & 8) == (follows[int(old)] is None)
 
 
 def test_sibling_pruning_and_merge_hand_example():
@@ -434,3 +461,50 @@ def test_sibling_pruning_and_merge_hand_example():
     assert origin.tolist() == [0, 1, 2, 3, 4, 5]
     assert flags.tolist() == [0, 0, 3, 0, 4, 0]
     assert p_off.tolist() == [0, 1, 2, 3, 4, 5, 7] and p_idx.tolist() == [-1, -1, -1, 0, 1, 3, 4]
+
+
+def test_cross_depth_merge_hand_example():
+    """tests/golden/hand_merge8.txt: a same-layer merge, a refused (cyclic) one and a merge into an earlier layer that
+    forces the renumbering; worked out by hand from Section 5.3."""
+    import os
+    from helpers import load_hand_dag
+    h = load_hand_dag(os.path.join(os.path.dirname(__file__), "golden", "hand_merge8.txt"))
+    par = np.asarray(h["tree_parent"], dtype=np.int32)
+    tok = np.asarray(h["tokens"], dtype=np.int32)
+    q = np.full(len(par), 0.5, dtype=np.float32)
+    p_off, p_idx, origin, flags = graph_one(par, tok, q, h["tau"][0], 0.0, 0.0)
+    assert origin.tolist() == h["origin"]
+    assert flags.tolist() == h["flags"]
+    assert p_off.tolist() == h["parent_offsets"].tolist() and p_idx.tolist() == h["parent_idx"].tolist()
+    # and the hypotheses listed in the fixture's last line
+    o, tpar, torg, cnt = gsd_next.unmerge_to_tree([0, len(origin)], p_off, p_idx, 1000)
+    spelled = set()
+    for t in range(len(tpar)):
+        seq, v = "", t
+        while v != -1:
+            seq = chr(int(tok[origin[torg[v]]])) + seq
+            v = int(tpar[v])
+        spelled.add(seq)
+    assert spelled == set("A B AB AC BA BD ABA ABD ACE BDC ABDC BDCE ABDCE".split())
+
+
+def test_pruning_thresholds_are_strict_and_compared_in_fp32():
+    """The library takes its thresholds as fp32 and the probabilities come as fp32: a probability exactly at the
+    (fp32) threshold stays, the next fp32 number below it is pruned; likewise for the sibling rule, whose threshold is
+    the fp32 product theta_sib * max."""
+    theta_p, theta_s = 0.2, 0.3
+    at_p = np.float32(theta_p)
+    below_p = np.nextafter(at_p, np.float32(0))
+    big = np.float32(0.9)
+    at_s = np.float32(theta_s) * big
+    below_s = np.nextafter(at_s, np.float32(0))
+    assert float(at_p) > theta_p and float(at_s) != theta_s * float(big)      # fp64 would decide differently somewhere
+    # root -> 0 (big), 1 (exactly theta_s*big), 2 (just below it), 3 (exactly theta_p: but below the sibling bar)
+    par = np.array([-1, -1, -1, -1], dtype=np.int32)
+    tok = np.array([1, 2, 3, 4], dtype=np.int32)
+    q = np.array([big, at_s, below_s, at_p], dtype=np.float32)
+    _, _, _, flags = graph_one(par, tok, q, 9, theta_p, theta_s)
+    assert flags.tolist() == [0, 0, 2, 2]
+    q = np.array([at_p, below_p, at_p, at_p], dtype=np.float32)                # sibling bar 0.3 * ~0.2: nobody below it
+    _, _, _, flags = graph_one(par, tok, q, 9, theta_p, theta_s)
+    assert flags.tolist() == [0, 1, 0, 0]
