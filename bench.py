@@ -344,8 +344,27 @@ def bench_build_graph(gsd, w, dev, stream, reps=20):
             res = gsd.gsd_build_token_graph(d_no, d_par, d_tok, d_q, n, tau, tp, ts)
         ms = time_launches(stream, call, reps)
         counts = res[5].cpu().numpy()
+        # what the merging did, read off the returned graph: an edge whose parent is not the child's tree parent is a
+        # merge edge; it goes into an earlier layer when that parent lies at or below the child's own tree depth
+        g_off, p_off, p_idx, origin, flags = (x.cpu().numpy() for x in res[:5])
+        merge_edges = cross = 0
+        for b in range(cfg.batch):
+            lo, hi = int(g_off[b]), int(g_off[b + 1])
+            tree_par = np.asarray(par[node_offsets[b]:node_offsets[b + 1]])
+            depth = np.zeros(len(tree_par), dtype=np.int64)
+            for i_, p_ in enumerate(tree_par):
+                depth[i_] = 1 if p_ < 0 else depth[p_] + 1
+            org = origin[lo:hi]
+            for g in range(lo, hi):
+                for r in p_idx[p_off[g]:p_off[g + 1]]:
+                    if r >= 0 and org[r] != tree_par[org[g - lo]]:
+                        merge_edges += 1
+                        cross += int(depth[org[r]] >= depth[org[g - lo]])
+        fl = flags[:int(g_off[-1])]
         out[name] = {"theta_prob": tp, "theta_sib": ts, "graph_nodes": int(counts[:, 0].sum()),
-                     "graph_edges": int(counts[:, 1].sum()), "avg_call_ms": ms}
+                     "graph_edges": int(counts[:, 1].sum()), "redundant_nodes": int(((fl & 4) != 0).sum()),
+                     "redundant_without_merge_edges": int(((fl & 8) != 0).sum()), "merge_edges": merge_edges,
+                     "merge_edges_into_earlier_layers": cross, "avg_call_ms": ms}
     out["trees"] = f"{cfg.batch} token trees of {n} nodes, out-degree <= {k}, alphabet {vocab}, tau {tau}"
     out["tree_nodes"] = int(node_offsets[-1])
     return out

@@ -294,18 +294,21 @@ int gsd_accept_stochastic(const gsd_stochastic_desc *desc, void *hip_stream);
  *   - it becomes a leaf if draft_prob < theta_prob, or if draft_prob < theta_sib * (largest draft_prob among its
  *     parent's children), both compared in fp32;
  *   - it is tau-redundant, and a leaf, if its depth is >= tau and its tau-gram (its token and those of its tau-1
- *     nearest ancestors) equals that of an earlier existing node; the earliest such node F is the first occurrence.
- *     If F is in the same layer, F's children (generated next) also get the redundant node as a parent: the merge
- *     edge.  If F is in an earlier layer no edge is drawn (F's children exist already; edges back into earlier layers
- *     could close cycles, a case the paper leaves open);
+ *     nearest ancestors in the tree) equals that of an earlier existing node; the earliest such node F is the first
+ *     occurrence.  Merging: the redundant node R becomes one more parent of every child of F, whichever layer F lies
+ *     in, so that what follows F is reused below R (the edge Section 5.3 draws from R to F).  The exception is an R
+ *     that already descends from F in the graph built so far (all parent edges, earlier merge edges included): the
+ *     reuse would close a cycle, a case the paper leaves open; such an R is a leaf without merge edges;
  *   - a node is expanded iff it is no leaf.
- * Existing nodes keep their order (a topological order of the result), so the output is a valid graph for every call
- * in this header.
+ * A merge into an earlier layer gives an existing node a parent that was generated after it, so the graph is renumbered
+ * into a topological order: by level (0 for the children of the root, otherwise one more than the largest level among
+ * the parents), nodes of one level in generation order.  Without such edges this is the generation order.  The output
+ * is a valid graph for every call in this header.
  *
  *   tau >= 1; counts [B][2] int32 out (nodes and edges of each sequence's graph)
  *   graph_node_offsets [B+1], parent_offsets [T+1] (only the first T'+1 entries are written), parent_idx
  *   [edge_capacity] (new sequence-local ids, ascending within a node, -1 = root), origin [T] (tree id of each graph
- *   node), flags [T]: bit0 probability-pruned, bit1 sibling-pruned, bit2 redundant, bit3 redundant without merge edge
+ *   node), flags [T]: bit0 probability-pruned, bit1 sibling-pruned, bit2 redundant, bit3 redundant without merge edges (cyclic case)
  *   error_flag [1] or NULL: bit0 set on malformed input (a parent id >= its child or < -1, ids not breadth first, more
  *   than max_nodes nodes; such nodes are dropped), bit1 if edge_capacity was too small (parent_idx is then incomplete).
  *   Never cleared.  Two launches on `hip_stream`; read graph_node_offsets / parent_offsets back to size what follows.

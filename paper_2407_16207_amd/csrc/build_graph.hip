@@ -10,8 +10,17 @@
 // level by level with one all-pairs comparison per level (the candidates of a wave sit one per lane and are
 // broadcast with readlane, so the comparison touches no memory).  During the walk the smallest existing node of
 // every class is kept in a table (atomic min by the layer's existing nodes), so "the earliest existing earlier node
-// with the same tau-gram" is one read.  A redundant node whose first occurrence lies in its own layer is merged
-// into it: the children of that node get one more parent.
+// with the same tau-gram" is one read.
+//
+// Merging (Section 5.3: an edge from the redundant node R to the first occurrence F of its tau-gram, so that what
+// follows F is reused below R) makes R one more parent of every child of F, unless R already descends from F in the
+// graph built so far: that would close a cycle, and R then stays a bare leaf.  Which nodes exist does not depend on
+// these decisions, but the decisions depend on each other in generation order (an edge drawn for one node changes
+// who descends from whom for the next), so after the walk the redundant nodes are taken one at a time, in id order,
+// against per-node ancestor bit rows in LDS: one bit test, then every descendant of F takes over R's ancestors, one
+// barrier per redundant node.  An edge from a later layer into an earlier one breaks the generation order as a
+// topological order: the fill kernel renumbers the graph by level (longest distance from the root, by relaxation),
+// nodes of one level in generation order.
 // Two launches: the first only counts nodes and edges per sequence, the second repeats the construction and writes
 // the packed graph behind the sequences before it (the library keeps no scratch memory).
 #include "gsd_internal.h"
@@ -25,16 +34,19 @@ struct GraphLds {
     int32_t tok[GSD_MAX_NODES_PER_SEQ];
     float q[GSD_MAX_NODES_PER_SEQ];
     int32_t depth[GSD_MAX_NODES_PER_SEQ];
-    int32_t flags[GSD_MAX_NODES_PER_SEQ];      // bit0 prob, bit1 sibling, bit2 redundant, bit3 no merge edge, bit8 exists
-    int32_t merged_to[GSD_MAX_NODES_PER_SEQ];  // first occurrence this node is merged into, or -1
+    int32_t flags[GSD_MAX_NODES_PER_SEQ];      // bit0 prob, bit1 sibling, bit2 redundant, bit3 no merge edge, bit8 exists, bit9 merged
+    int32_t merged_to[GSD_MAX_NODES_PER_SEQ];  // first occurrence of a redundant node's tau-gram, or -1
     uint32_t sib_max[GSD_MAX_NODES_PER_SEQ + 1];   // float bits of the largest child probability, slot p+1
     int32_t scan[GSD_MAX_NODES_PER_SEQ];
     int32_t cls[GSD_MAX_NODES_PER_SEQ];        // class of the node's tau-gram (an earlier-or-equal node id), -1 if none
     int32_t first_ex[GSD_MAX_NODES_PER_SEQ];   // per class: smallest existing node seen so far
-    int32_t merge_cnt[GSD_MAX_NODES_PER_SEQ];  // nodes merged into this one
+    int32_t merge_cnt[GSD_MAX_NODES_PER_SEQ];  // nodes merged into this one (merge edges actually drawn)
+    uint64_t anc[GSD_MAX_NODES_PER_SEQ * 8];   // ancestor bit row of every node in the graph built so far (itself included)
     int32_t bad;
     int32_t max_depth;
 };
+constexpr int kFlagExists = 0x100;             // internal flag bits, above the four that are returned
+constexpr int kFlagMerged = 0x200;             // redundant node whose merge edges are drawn
 
 // Runs the construction for the calling work-group's sequence; afterwards flags (bit8 = exists), merged_to and depth
 // are final.  Returns the node count through n_out.
@@ -127,10 +139,10 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
         bool ex = false;
         if (my_depth == layer) {
             const int p = s.par[i];
-            ex = p == -1 || (p >= 0 && (s.flags[p] & 0x100) && (s.flags[p] & 0xf) == 0);
+            ex = p == -1 || (p >= 0 && (s.flags[p] & kFlagExists) && (s.flags[p] & 0xf) == 0);
             int f = 0;
             if (ex) {
-                f = 0x100;
+                f = kFlagExists;
                 if (s.q[i] < theta_prob) f |= 1;
                 if (s.q[i] < theta_sib * __uint_as_float(s.sib_max[p + 1])) f |= 2;
             }
@@ -144,13 +156,8 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
         if (my_depth == layer && ex && layer >= tau) {
             const int first = s.first_ex[my_cls];
             if (first < i) {
-                if (s.depth[first] == layer) {
-                    s.merged_to[i] = first;
-                    atomicAdd(&s.merge_cnt[first], 1);
-                    s.flags[i] |= 4;
-                } else {
-                    s.flags[i] |= 4 | 8;
-                }
+                s.merged_to[i] = first;
+                s.flags[i] |= 4;
             }
         }
         __syncthreads();
@@ -171,10 +178,52 @@ __device__ int block_scan(int32_t *buf, int value) {
     return buf[i];
 }
 
-// number of parents of existing node i in the graph beyond its tree parent: the nodes merged into that parent
-__device__ int extra_parents(const GraphLds &s, int n, int i) {
-    const int f = s.par[i];
-    return f < 0 ? 0 : s.merge_cnt[f];
+// After construct(): takes the redundant nodes in id order and decides for each whether its merge edges are drawn
+// (kFlagMerged, merge_cnt of the first occurrence) or it descends from its first occurrence (bit 3).  Leaves the
+// ancestor rows of the finished graph in s.anc.  Uses s.cls (free after construct) for the list of redundant nodes.
+__device__ void decide_merges(GraphLds &s, int n) {
+    const int i = threadIdx.x;
+    const bool ex = i < n && (s.flags[i] & kFlagExists);
+    uint64_t *row = s.anc + i * 8;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) row[w] = 0;
+    __syncthreads();
+    const int max_depth = s.max_depth;
+    for (int layer = 1; layer <= max_depth; ++layer) {      // tree ancestors: the parent's row plus the node itself
+        if (ex && s.depth[i] == layer) {
+            const int p = s.par[i];
+            if (p >= 0) {
+#pragma unroll
+                for (int w = 0; w < 8; ++w) row[w] = s.anc[p * 8 + w];
+            }
+            row[i >> 6] |= uint64_t(1) << (i & 63);
+        }
+        __syncthreads();
+    }
+    const bool red = ex && (s.flags[i] & 4);
+    const int pos = block_scan(s.scan, red ? 1 : 0) - 1;
+    const int n_red = s.scan[kGraphThreads - 1];
+    __syncthreads();
+    if (red) s.cls[pos] = i;
+    __syncthreads();
+    for (int k = 0; k < n_red; ++k) {                       // uniform trip count and operands
+        const int r = s.cls[k], f = s.merged_to[r];
+        const bool cyclic = (s.anc[r * 8 + (f >> 6)] >> (f & 63)) & 1;
+        if (!cyclic) {
+            // r is no descendant of f, so nobody writes r's row in this step; every other row is written by its owner
+            if (ex && i != f && ((row[f >> 6] >> (f & 63)) & 1)) {
+#pragma unroll
+                for (int w = 0; w < 8; ++w) row[w] |= s.anc[r * 8 + w];
+            }
+            if (i == r) {
+                s.flags[i] |= kFlagMerged;
+                s.merge_cnt[f] += 1;
+            }
+        } else if (i == r) {
+            s.flags[i] |= 8;
+        }
+        __syncthreads();
+    }
 }
 
 __global__ __launch_bounds__(kGraphThreads) void graph_count_kernel(
@@ -192,12 +241,13 @@ __global__ __launch_bounds__(kGraphThreads) void graph_count_kernel(
     }
     if (n < 0) n = 0;
     construct(s, n, base, tree_parent, tokens, draft_prob, tau, theta_prob, theta_sib);
+    decide_merges(s, n);
     const int i = threadIdx.x;
-    const bool ex = i < n && (s.flags[i] & 0x100);
+    const bool ex = i < n && (s.flags[i] & kFlagExists);
     const int nodes = block_scan(s.scan, ex ? 1 : 0);
     const int total_nodes = s.scan[kGraphThreads - 1];
     __syncthreads();
-    const int edges = block_scan(s.scan, ex ? 1 + extra_parents(s, n, i) : 0);
+    const int edges = block_scan(s.scan, ex ? 1 + (s.par[i] >= 0 ? s.merge_cnt[s.par[i]] : 0) : 0);
     const int total_edges = s.scan[kGraphThreads - 1];
     (void)nodes;
     (void)edges;
@@ -244,35 +294,95 @@ __global__ __launch_bounds__(kGraphThreads) void graph_fill_kernel(
     if (n > max_nodes) n = max_nodes;
     if (n < 0) n = 0;
     construct(s, n, base, tree_parent, tokens, draft_prob, tau, theta_prob, theta_sib);
-    const bool ex = i < n && (s.flags[i] & 0x100);
-    const int my_new = block_scan(s.scan, ex ? 1 : 0) - 1;           // new id of an existing node
+    decide_merges(s, n);
+    const bool ex = i < n && (s.flags[i] & kFlagExists);
+    const bool merger = ex && (s.flags[i] & kFlagMerged);
+    const int my_par = i < n ? s.par[i] : -2;
+    const int my_first = merger ? s.merged_to[i] : -1;
+    // Storage that construct() and decide_merges() are done with is used again from here on:
+    int32_t *level = s.tok;                 // longest distance from the root, in edges below the root's children
+    int32_t *group_level = s.first_ex;      // per node f: the largest level among f and the nodes merged into it
+    int32_t *new_id = reinterpret_cast<int32_t *>(s.q);
+    int32_t *list_off = reinterpret_cast<int32_t *>(s.sib_max);     // per f: where its mergers' new ids start in `list`
+    int32_t *list = s.cls;                  // new ids of the mergers of every f, ascending within an f
+    __syncthreads();
+    level[i] = ex ? s.depth[i] - 1 : -1;
+    group_level[i] = -1;
+    __syncthreads();
+    // levels by relaxation: they start at the tree depth, a lower bound, and only grow; a sweep that moves nothing
+    // ends it (at most one sweep per node of the longest path, and never more than n + 1)
+    for (int sweep = 0; sweep <= n; ++sweep) {
+        if (ex) atomicMax(&group_level[i], level[i]);
+        if (merger) atomicMax(&group_level[my_first], level[i]);
+        __syncthreads();
+        int changed = 0;
+        if (ex && my_par >= 0) {
+            const int l = 1 + group_level[my_par];
+            if (l > level[i]) {
+                level[i] = l;
+                changed = 1;
+            }
+        }
+        if (!__syncthreads_or(changed)) break;
+    }
+    // new id = rank by (level, id) among the existing nodes
+    int my_new = -1;
+    if (ex) {
+        my_new = 0;
+        const int li = level[i];
+        for (int j = 0; j < n; ++j) {
+            const int lj = level[j];
+            my_new += (lj >= 0 && (lj < li || (lj == li && j < i))) ? 1 : 0;
+        }
+    }
+    new_id[i] = my_new;
+    (void)block_scan(s.scan, ex ? 1 : 0);
     const int total_nodes = s.scan[kGraphThreads - 1];
     __syncthreads();
-    // new ids of all nodes are needed below: keep them where depth is no longer read... depth IS read by
-    // extra_parents, so the ids go into q's storage (reinterpreted) once q is done with
-    int32_t *new_id = reinterpret_cast<int32_t *>(s.q);
+    // the mergers of every first occurrence, sorted by new id
+    const int cnt_i = i < n ? s.merge_cnt[i] : 0;
+    const int off_end = block_scan(s.scan, cnt_i);
     __syncthreads();
-    if (i < n) new_id[i] = ex ? my_new : -1;
+    list_off[i] = off_end - cnt_i;
     __syncthreads();
-    const int my_edges = ex ? 1 + extra_parents(s, n, i) : 0;
-    const int edge_end = block_scan(s.scan, my_edges);
+    if (merger) {
+        int before = 0;
+        for (int j = 0; j < n; ++j)
+            before += ((s.flags[j] & kFlagMerged) && s.merged_to[j] == my_first && new_id[j] < my_new) ? 1 : 0;
+        list[list_off[my_first] + before] = my_new;
+    }
+    __syncthreads();
+    // edges, in the order of the new ids
+    const int my_edges = ex ? 1 + (my_par >= 0 ? s.merge_cnt[my_par] : 0) : 0;
+    int32_t *by_rank = s.depth;             // depth is not read any more
+    by_rank[i] = 0;
+    __syncthreads();
+    if (ex) by_rank[my_new] = my_edges;
+    __syncthreads();
+    (void)block_scan(s.scan, by_rank[i]);
     const int total_edges = s.scan[kGraphThreads - 1];
     if (ex) {
         const int g = node_base + my_new;
         origin[g] = i;
         flags_out[g] = s.flags[i] & 0xf;
-        parent_offsets[g] = edge_base + edge_end - my_edges;
-        int64_t e = int64_t(edge_base) + edge_end - my_edges;
-        const int f = s.par[i];
+        int64_t e = int64_t(edge_base) + s.scan[my_new] - my_edges;
+        parent_offsets[g] = int32_t(e);
         bool over = false;
         auto put = [&](int32_t v) {
             if (e < edge_capacity) parent_idx[e] = v; else over = true;
             ++e;
         };
-        put(f < 0 ? -1 : new_id[f]);
-        if (f >= 0 && s.merge_cnt[f] > 0)              // the nodes merged into the parent, in id order
-            for (int r = f + 1; r < n && s.depth[r] == s.depth[f]; ++r)
-                if (s.merged_to[r] == f) put(new_id[r]);
+        if (my_par < 0) {
+            put(-1);
+        } else {                                // the tree parent's new id merged into the sorted ids of its mergers
+            const int pid = new_id[my_par];
+            const int k = s.merge_cnt[my_par];
+            const int32_t *m = list + list_off[my_par];
+            int x = 0;
+            for (; x < k && m[x] < pid; ++x) put(m[x]);
+            put(pid);
+            for (; x < k; ++x) put(m[x]);
+        }
         if (over && error_flag) atomicOr(error_flag, 2);
     }
     if (i == 0) {

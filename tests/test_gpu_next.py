@@ -387,6 +387,49 @@ def test_build_token_graph_matches_oracle(gpu, tau, theta_prob, theta_sib):
     assert rflag == 0 and np.array_equal(gpu.mask_to_numpy(mask), rmask)
 
 
+def compare_graph_with_oracle(gpu, node_offsets, par, tok, q, tau, theta_prob, theta_sib, max_nodes=512):
+    import paper_2407_16207_amd as gsd
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda")
+    r = gsd_next.build_token_graph(node_offsets, par, tok, q, tau, theta_prob, theta_sib)
+    g_off, p_off, p_idx, origin, flags, counts = gsd.gsd_build_token_graph(
+        gpu.to_dev(node_offsets), gpu.to_dev(par), gpu.to_dev(tok), gpu.to_dev(q), max_nodes, tau, theta_prob, theta_sib,
+        edge_capacity=max(16, len(r[2])), error_flag=flag)
+    torch.cuda.synchronize()
+    assert flag.item() == 0
+    g_off = g_off.cpu().numpy()
+    Tn = int(g_off[-1])
+    assert np.array_equal(g_off, r[0])
+    assert np.array_equal(p_off.cpu().numpy()[:Tn + 1], r[1])
+    assert np.array_equal(p_idx.cpu().numpy()[:len(r[2])], r[2])
+    assert np.array_equal(origin.cpu().numpy()[:Tn], r[3]) and np.array_equal(flags.cpu().numpy()[:Tn], r[4])
+    return r
+
+
+def test_build_token_graph_hand_example_with_a_merge_into_an_earlier_layer(gpu):
+    """tests/golden/hand_merge8.txt (worked out by hand from Section 5.3) through the kernel."""
+    import os
+    from helpers import load_hand_dag
+    h = load_hand_dag(os.path.join(os.path.dirname(__file__), "golden", "hand_merge8.txt"))
+    par, tok = np.asarray(h["tree_parent"], dtype=np.int32), np.asarray(h["tokens"], dtype=np.int32)
+    r = compare_graph_with_oracle(gpu, np.array([0, len(par)], dtype=np.int32), par, tok,
+                                  np.full(len(par), 0.5, dtype=np.float32), h["tau"][0], 0.0, 0.0, max_nodes=8)
+    assert r[3].tolist() == h["origin"] and r[4].tolist() == h["flags"] and r[2].tolist() == h["parent_idx"].tolist()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_build_token_graph_random_trees(gpu, seed):
+    """Trees of many shapes and alphabets: merges within a layer, into earlier layers, refused (cyclic) ones, graphs
+    that have to be renumbered, first occurrences with dozens of merged nodes."""
+    rng = np.random.default_rng(7000 + seed)
+    sizes = [int(x) for x in rng.integers(1, 513, 5)] + [512]
+    k, vocab, tau = int(rng.integers(2, 5)), int(rng.integers(2, 30)), int(rng.integers(1, 4))
+    node_offsets, par, tok, q = token_trees(rng, sizes, k, vocab)
+    tp, ts = (0.0, 0.0) if seed % 3 else (0.05, 0.2)
+    r = compare_graph_with_oracle(gpu, node_offsets, par, tok, q, tau, tp, ts)
+    print(f"[graph] seed {seed}: k {k} vocab {vocab} tau {tau}: {int(r[0][-1])} nodes, {len(r[2])} edges, "
+          f"{int(((r[4] & 4) != 0).sum())} redundant, {int(((r[4] & 8) != 0).sum())} of them cyclic", flush=True)
+
+
 def test_build_token_graph_flags_bad_input_and_small_capacity(gpu):
     import paper_2407_16207_amd as gsd
     par = np.array([-1, 0, 3, 0, -5, 1], dtype=np.int32)          # node 2 points forward, node 4 below -1
