@@ -102,10 +102,19 @@ def cpu_baseline(w, sample_nodes: int):
                         "accept_full": t_accept}}
 
 
-def time_launches(stream, fn, reps, warmup=10):
+def time_launches(stream, fn, reps, warmup=10, warm_ms=40.0):
+    """Average duration of `reps` launches of fn, HIP events on `stream`.  Warm-up: at least `warmup` launches and at
+    least `warm_ms` of GPU work: after host-side preparation (graph generation, allocation) the chip has dropped its
+    clocks, and a short burst measured right away comes out up to 15 % slow (seen on this chip: the same attention
+    launch 306 us in a 30-launch burst after idling, 261 us once busy)."""
     import torch
-    for i in range(warmup):
+    t0 = time.perf_counter()
+    i = 0
+    while i < warmup or (time.perf_counter() - t0) * 1e3 < warm_ms:
         fn(i)
+        i += 1
+        if i % 8 == 0:
+            torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record(stream)
     for i in range(reps):
@@ -370,6 +379,39 @@ def bench_build_graph(gsd, w, dev, stream, reps=20):
     return out
 
 
+def bench_config5_dag_vs_tree(gsd, dev, reps=10):
+    """Config 5 (batch 32, ragged prefixes, 512 draft nodes per sequence): the attention launch on its layered token
+    graph and on the same-size token tree (every node keeps its first parent only: Section 4.1's tree attention
+    against Section 5.3's graph), same Q/K/V: time, algorithmic flops and rate of both."""
+    import numpy as np
+    import torch
+    from paper_2407_16207_amd.workload import make_workload
+    wd = make_workload(5, with_logits=False)
+    wt = make_workload(5, with_logits=False, with_qkv=False, tree=True)
+    cfg = wd.cfg
+    q, k, v = dev(wd.q), dev(wd.k), dev(wd.v)
+    kv_offsets, prefix_lens, node_offsets = dev(wd.kv_offsets), dev(wd.prefix_lens), dev(wd.node_offsets)
+    out = torch.empty_like(q)
+    stream = torch.cuda.current_stream()
+    res = {"workload": cfg.name, "kv_prefix": [int(wd.prefix_lens.min()), int(wd.prefix_lens.max())],
+           "total_nodes": wd.total_nodes}
+    for name, w in (("graph", wd), ("tree", wt)):
+        mask = gsd.gsd_build_mask(node_offsets, dev(w.parent_offsets), dev(w.parent_idx), w.max_nodes)
+        desc = gsd.make_attn_desc(q, k, v, kv_offsets, prefix_lens, node_offsets, mask, w.max_nodes,
+                                  int(wd.prefix_lens.max()), wd.softmax_scale, out=out)
+        assert gsd.gsd_dag_attention_workspace(desc) == 0
+        ms = time_launches(stream, lambda i: gsd.gsd_dag_attention_desc(desc), reps, warmup=3)
+        vis = popcount_rows(mask.cpu().numpy().view(np.uint64))
+        keys = np.repeat(wd.prefix_lens.astype(np.int64), np.diff(wd.node_offsets)) + vis
+        flops = 4.0 * cfg.head_dim * cfg.num_q_heads * float(keys.sum())
+        res[name] = {"attention_ms": ms, "flops": flops, "tflops": flops / ms / 1e9,
+                     "frac_of_bf16_mfma_peak": flops / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+                     "mean_visible_draft_nodes": float(vis.mean()), "edges": int(len(w.parent_idx))}
+    res["tree_over_graph"] = {"flops": res["tree"]["flops"] / res["graph"]["flops"],
+                              "time": res["tree"]["attention_ms"] / res["graph"]["attention_ms"]}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -609,6 +651,8 @@ def main():
         result["unmerge_to_tree"] = bench_unmerge(gsd, w, dev, stream)
         result["stochastic_verify"] = bench_stochastic(gsd, w, dev, logits, stream)
         result["build_token_graph"] = bench_build_graph(gsd, w, dev, stream)
+        if cfg.name.startswith("cfg4"):
+            result["config5_dag_vs_tree"] = bench_config5_dag_vs_tree(gsd, dev)
         result["matrix_pipe_sustained"] = bench_matrix_pipe(gsd, w, q, k, v, kv_offsets, prefix_lens, node_offsets,
                                                             mask, out, workspace, need, flops, stream, args.splits)
         result["roofline"]["achieved_over_bare_mfma_loop_same_operand_statistics"] = (

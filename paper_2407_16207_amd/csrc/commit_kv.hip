@@ -2,53 +2,67 @@
 //
 // Per sequence, layer and K|V the accepted draft rows are compacted in place behind the prefix:
 //     row P+j <- row P+path[j],  j = 0 .. accept_len-1,  path strictly increasing so path[j] >= j.
-// HBM-bound: 2 * accept_len * row_bytes bytes per (sequence, layer, K|V).  A thread owns one 16-byte column of
-// the rows and walks j upwards in groups of kGroup: it loads the group's source rows, then stores them.  Because
-// a destination j is never above its source and sources only grow, a row is always read (by this thread, in this
-// column) before anything overwrites it; different columns never touch each other's bytes, so no
-// synchronisation is needed at all.
+// HBM-bound: 2 * (rows that move) * row_bytes bytes per (sequence, layer, K|V).  A work-group owns up to 256 of the
+// 16-byte columns of one (sequence, layer, K|V) and takes the destination rows in chunks of 4096/columns rows: every
+// thread loads its 16 (row, column) pieces of the chunk, all loads in flight at once, the work-group meets at a
+// barrier, then every thread stores.  In place is safe: a source row is never below its destination and sources only
+// grow, so a chunk reads rows at or above its first destination row and writes only its own destination rows after
+// the barrier, and the chunks that follow read only rows above those.  Different columns never touch each other's
+// bytes.  Rows already in place (path[j] == j) are neither read nor written.
 #include "gsd_internal.h"
 
 namespace gsd {
 
 constexpr int kCommitThreads = 256;
-constexpr int kGroup = 8;
+constexpr int kPieces = 16;                                   // 16-byte pieces a thread holds between load and store
+constexpr int kChunkPieces = kCommitThreads * kPieces;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // (HIP's uint4 class keeps such arrays out of registers)
 
 __global__ __launch_bounds__(kCommitThreads) void commit_kv_kernel(
     int32_t max_nodes, int vecs_per_row, char *__restrict__ k, char *__restrict__ v, int64_t token_stride,
     int64_t layer_stride, const int64_t *__restrict__ kv_offsets, const int32_t *__restrict__ prefix_lens,
     const int32_t *__restrict__ accept_len, const int32_t *__restrict__ accept_path,
     int32_t *__restrict__ new_prefix_lens) {
+    __shared__ int32_t src_of[GSD_MAX_NODES_PER_SEQ];         // source row of destination row j, or -1: nothing to move
     const int b = blockIdx.z >> 1;
     const int which = blockIdx.z & 1;
     const int layer = blockIdx.y;
-    const int col = blockIdx.x * kCommitThreads + threadIdx.x;
+    const int col0 = blockIdx.x * kCommitThreads;
+    const int cols = min(kCommitThreads, vecs_per_row - col0);          // >= 1 by the grid's construction
     int len = accept_len[b];
     if (len > max_nodes) len = max_nodes;
     const int P = prefix_lens[b];
-    if (which == 0 && layer == 0 && col == 0) new_prefix_lens[b] = P + (len > 0 ? len : 0);
-    if (col >= vecs_per_row || len <= 0) return;
+    if (which == 0 && layer == 0 && blockIdx.x == 0 && threadIdx.x == 0) new_prefix_lens[b] = P + (len > 0 ? len : 0);
+    if (len <= 0) return;                                               // uniform for the work-group
 
-    char *rows = (which ? v : k) + layer * layer_stride + (kv_offsets[b] + P) * token_stride + int64_t(col) * 16;
     const int32_t *path = accept_path + int64_t(b) * max_nodes;
-    for (int j0 = 0; j0 < len; j0 += kGroup) {
-        uint4 held[kGroup];
-        bool move[kGroup];
+    for (int j = threadIdx.x; j < len; j += kCommitThreads) {
+        const int s = path[j];
+        src_of[j] = (s > j && s < max_nodes) ? s : -1;                 // s == j: already in place
+    }
+    __syncthreads();
+
+    char *rows = (which ? v : k) + layer * layer_stride + (kv_offsets[b] + P) * token_stride + int64_t(col0) * 16;
+    const int rows_per_chunk = kChunkPieces / cols;                     // >= kPieces
+    for (int j0 = 0; j0 < len; j0 += rows_per_chunk) {
+        const int pieces = min(rows_per_chunk, len - j0) * cols;
+        u32x4 held[kPieces];
+        int64_t dst[kPieces];                                           // byte offset of the destination, -1: no store
+        // loads without branches: a piece that does not exist or does not move reads its own destination instead
 #pragma unroll
-        for (int x = 0; x < kGroup; ++x) {
-            const int j = j0 + x;
-            move[x] = false;
-            if (j < len) {
-                const int s = path[j];
-                if (s > j && s < max_nodes) {              // s == j: already in place
-                    held[x] = *reinterpret_cast<const uint4 *>(rows + int64_t(s) * token_stride);
-                    move[x] = true;
-                }
-            }
+        for (int x = 0; x < kPieces; ++x) {
+            const int idx = min(int(threadIdx.x) + x * kCommitThreads, pieces - 1);
+            const int r = idx / cols, c = idx - r * cols;
+            const int j = j0 + r;
+            const int s = src_of[j];
+            const bool moves = s >= 0 && int(threadIdx.x) + x * kCommitThreads < pieces;
+            dst[x] = moves ? int64_t(j) * token_stride + c * 16 : -1;
+            held[x] = *reinterpret_cast<const u32x4 *>(rows + int64_t(moves ? s : j) * token_stride + c * 16);
         }
+        __syncthreads();                                                // every source of the chunk has been read
 #pragma unroll
-        for (int x = 0; x < kGroup; ++x)
-            if (move[x]) *reinterpret_cast<uint4 *>(rows + int64_t(j0 + x) * token_stride) = held[x];
+        for (int x = 0; x < kPieces; ++x)
+            if (dst[x] >= 0) *reinterpret_cast<u32x4 *>(rows + dst[x]) = held[x];
     }
 }
 
