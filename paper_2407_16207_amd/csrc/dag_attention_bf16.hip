@@ -110,6 +110,12 @@ __device__ __forceinline__ void dma16(const void *gbase, uint32_t voff, uint32_t
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
                  :: "s"(gbase), "v"(voff), "s"(lds_base) : "memory");
 }
+// The same with the LDS address as a scalar base plus a constant, added inside: given one scalar per destination
+// the compiler keeps them all live across the loop (sixteen at four copies per tile and wave) and spills them.
+__device__ __forceinline__ void dma16_at(const void *gbase, uint32_t voff, uint32_t lds_base, int lds_const) {
+    asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
+                 :: "s"(gbase), "v"(voff), "s"(lds_base), "i"(lds_const) : "memory", "scc");
+}
 template <int N> __device__ __forceinline__ void dma_wait() {   // at most N vector-memory operations in flight
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
@@ -329,6 +335,7 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     const __bf16 *v_seq = p.v + kv_elem_off;
     const uint32_t row_stride_bytes = uint32_t(p.kv_ts) * 2u;
     const int32_t last_row = P + n - 1;            // last K/V row of the sequence: loads are clamped to it
+    const uint32_t wave_lds = lds_base + wave * IPW * 1024;     // where this wave's first copy of a tile lands in buffer 0
     // Copy j = 0 decides everything: later copies only add compile-time constants (rows) or flip one chunk bit.
     const int32_t m0 = wave * IPW * RPI + lane / CHUNKS;          // LDS row position filled by copy 0
     const int slot = lane % CHUNKS;
@@ -342,12 +349,11 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         // source row of LDS position m0 + j*RPI: the row permutation is bitwise, and m0, j*RPI share no bits
         const uint32_t r = uint32_t(min(tile_first_row(ti) + k_lds_row(m0) + k_lds_row(j * RPI), last_row));
         const uint32_t chunk = k_src_chunk0 ^ uint32_t(k_swz(j * RPI) * 16);
-        dma16(k_seq, __umul24(r, row_stride_bytes) + chunk, lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
+        dma16_at(k_seq, __umul24(r, row_stride_bytes) + chunk, wave_lds + buf * L::kTileBytes, j * 1024);
     };
     auto dma_v_one = [&](int ti, int buf, int j) __attribute__((always_inline)) {
         const uint32_t r = uint32_t(min(tile_first_row(ti) + m0 + j * RPI, last_row));
-        dma16(v_seq, __umul24(r, row_stride_bytes) + v_src_chunk,
-              lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
+        dma16_at(v_seq, __umul24(r, row_stride_bytes) + v_src_chunk, wave_lds + (2 + buf) * L::kTileBytes, j * 1024);
     };
     // The same copies over a run of consecutive full prefix tiles (all 64 rows exist, no clamp): every lane keeps
     // the byte offset of its next chunk and adds one tile's worth after each copy, which is all the address
@@ -363,11 +369,11 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         }
     };
     auto dma_k_one_full = [&](int buf, int j) __attribute__((always_inline)) {
-        dma16(k_seq, k_run[j], lds_base + buf * L::kTileBytes + (wave * IPW + j) * 1024);
+        dma16_at(k_seq, k_run[j], wave_lds + buf * L::kTileBytes, j * 1024);
         k_run[j] += tile_stride_bytes;
     };
     auto dma_v_one_full = [&](int buf, int j) __attribute__((always_inline)) {
-        dma16(v_seq, v_run[j], lds_base + (2 + buf) * L::kTileBytes + (wave * IPW + j) * 1024);
+        dma16_at(v_seq, v_run[j], wave_lds + (2 + buf) * L::kTileBytes, j * 1024);
         v_run[j] += tile_stride_bytes;
     };
     auto dma_k = [&](int ti, int buf) __attribute__((always_inline)) {
@@ -513,6 +519,22 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     auto convert_pair = [&](floatx16 (&sc)[2], int e, float &sum, int rb) __attribute__((always_inline)) {
         convert_pair_with(sc, e, sum, rb, nm[rb]);
     };
+    // The same one score at a time, for the loop: the vector work is dealt out evenly, one score behind every matrix
+    // instruction (an even score waits in x_hold for its odd neighbour, with which it is packed).
+    float x_hold[RBW];
+    auto convert_one = [&](floatx16 (&sc)[2], int e, float &sum, int rb) __attribute__((always_inline)) {
+        const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e / 16][e % 16], c_log2, nm[rb]));
+        sum += x;
+        asm volatile("" : "+v"(sum));
+        if (e & 1) {
+            floatx2 xx;
+            xx[0] = x_hold[rb];
+            xx[1] = x;
+            pf[rb][e / 8][(e / 2) % 4] = __builtin_bit_cast(uint32_t, __builtin_convertvector(xx, bf16x2));
+        } else {
+            x_hold[rb] = x;
+        }
+    };
     // The exponentials are the vector ALU's heaviest load, so they are split between the two phases: phase B of
     // step i-1 converts scores 0..B_SCORES-1 of tile i (right after it has found the tile's max), phase A of step i
     // converts the rest.  A slice is one K or V fragment's worth of matrix instructions (one per row block).
@@ -523,7 +545,6 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     auto phase_a = [&](auto has_next_tag, auto full_tag, int kbuf, floatx16 (&sc)[RBW][2], floatx16 (&s_next)[RBW][2], int v_tile, int v_buf, int v_cur) __attribute__((always_inline)) {
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr bool FULL = decltype(full_tag)::value;     // the tile being copied is a full prefix tile
-        constexpr int PAIRS = (32 - B_SCORES) / 2 * RBW;   // pairs of scores converted here; pair q goes into slice q*NQK/PAIRS
         float sum[RBW];
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) sum[rb] = 0.f;
@@ -555,9 +576,8 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                     }
                 }
 #pragma unroll
-                for (int q = 0; q < PAIRS; ++q)
-                    if ((q * NQK) / PAIRS == idx && q % RBW == rb)
-                        convert_pair(sc[rb], B_SCORES + 2 * (q / RBW), sum[rb], rb);
+                for (int u = 0; u < 32 - B_SCORES; ++u)            // score B_SCORES + u goes into slice u*NQK/(32-B_SCORES)
+                    if ((u * NQK) / (32 - B_SCORES) == idx) convert_one(sc[rb], B_SCORES + u, sum[rb], rb);
                 GSD_SLICE_END();
             }
         }
@@ -591,9 +611,8 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         constexpr bool FULL = decltype(full_tag)::value;
         constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
         constexpr int CONV_FIRST = MBD;                 // first slice that converts: pf[.][0] is last read by slice MBD-1
-        constexpr int PAIRS = B_SCORES / 2 * RBW;       // pair q goes into slice CONV_FIRST + q*(NPV - CONV_FIRST)/PAIRS
-        // pf[.][1] is last read by slice 2*MBD-1 and may be rewritten only after that
-        static_assert(B_SCORES <= 8 || CONV_FIRST + ((4 * RBW) * (NPV - CONV_FIRST)) / PAIRS >= 2 * MBD,
+        // pf[.][1] (scores 8..15) is last read by slice 2*MBD-1 and is first rewritten when score 9 has been converted
+        static_assert(B_SCORES <= 8 || CONV_FIRST + (9 * (NPV - CONV_FIRST)) / B_SCORES >= 2 * MBD,
                       "probabilities of the current tile would be overwritten before they are used");
         if (__builtin_expect(pend_now | pend_next, 0)) {    // an offset moved one or two tiles ago
             if (pend_now) {
@@ -649,9 +668,9 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 }
                 if (HAS_NEXT) {
 #pragma unroll
-                    for (int q = 0; q < PAIRS; ++q)
-                        if (CONV_FIRST + (q * (NPV - CONV_FIRST)) / PAIRS == idx && q % RBW == rb)
-                            convert_pair(s_next[rb], 2 * (q / RBW), sum[rb], rb);
+                    for (int u = 0; u < B_SCORES; ++u)             // score u goes into slice CONV_FIRST + u*(NPV-CONV_FIRST)/B_SCORES
+                        if (CONV_FIRST + (u * (NPV - CONV_FIRST)) / B_SCORES == idx)
+                            convert_one(s_next[rb], u, sum[rb], rb);
                 }
                 GSD_SLICE_END();
             }
