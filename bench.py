@@ -591,6 +591,12 @@ def main():
     e1.record(stream)
     torch.cuda.synchronize()
     argmax_ms = e0.elapsed_time(e1) / reps
+    # the same sweep with the softmax normalisers folded in (what non-deterministic verification needs as well)
+    row_max = torch.empty(T, dtype=torch.float32, device="cuda")
+    row_sum = torch.empty(T, dtype=torch.float32, device="cuda")
+    fused_ms = time_launches(stream, lambda i: gsd.gsd_node_argmax_stats(logits, pred=pred, row_max=row_max,
+                                                                         row_sumexp=row_sum), reps, warmup=3,
+                             warm_ms=5.0)
 
     # algorithmic work of the attention launch: 4*D flops per visible (query row, key) pair
     vis = popcount_rows(mask.cpu().numpy().view(np.uint64))
@@ -625,6 +631,11 @@ def main():
         "roofline_argmax": {"kernel": "node_argmax_kernel", "bound": "hbm", "achieved": argmax_gbs,
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": argmax_gbs / HBM_PEAK_GBS,
                             "algorithmic_bytes_per_launch": logits_bytes, "avg_launch_ms": float(argmax_ms)},
+        "roofline_argmax_with_softmax_stats": {"kernel": "node_argmax_kernel<STATS>", "bound": "hbm",
+                                               "achieved": logits_bytes / (fused_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                                               "unit": "GB/s", "frac": logits_bytes / (fused_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                               "algorithmic_bytes_per_launch": logits_bytes,
+                                               "avg_launch_ms": float(fused_ms)},
         "attention_tflops": attn_tflops,
         "attention_pct_bf16_mfma_peak": 100.0 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
         "ms_per_step_by_hip_events": ms_per_step_events,

@@ -6,7 +6,8 @@
  *
  *   gsd_build_mask            token graph (DAG) -> per-node visibility bitmask (ancestor closure)
  *   gsd_dag_attention         masked attention of every packed draft node over [context ; visible nodes]
- *   gsd_node_argmax           the verifier's own next token after every node (row argmax of the logits)
+ *   gsd_node_argmax           the verifier's own next token after every node (row argmax of the logits);
+ *                             gsd_node_argmax_stats: the same sweep also leaves the softmax normalisers
  *   gsd_accept_longest_path   longest root path on which every drafted token equals the verifier's choice
  * and, around that pass,
  *   gsd_unmerge_to_tree       token graph -> token tree with replicated successors (Section 5.4), gsd_gather_rows
@@ -155,6 +156,17 @@ int gsd_dag_attention_static(const gsd_attn_desc *desc, void *hip_stream);
  */
 int gsd_node_argmax(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
                     int32_t *pred, void *hip_stream);
+
+/*
+ * gsd_node_argmax and gsd_softmax_stats (below) in ONE pass over the logits: the verifier's own token after every
+ * node (Section 3, deterministic verification) and the normaliser of its distribution there (Section 3, the
+ * probabilities non-deterministic verification compares), for callers that want both without reading the logits
+ * twice.  pred as gsd_node_argmax (bit-identical); row_max[r] = max_x logits[r][x], row_sumexp[r] = sum_x
+ * exp(logits[r][x] - row_max[r]) in fp32 (same definition as gsd_softmax_stats; the summation order differs, so the
+ * last bits may).  rows >= 1, vocab >= 1; pred [rows] int32; row_max, row_sumexp [rows] fp32.
+ */
+int gsd_node_argmax_stats(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
+                          int32_t *pred, float *row_max, float *row_sumexp, void *hip_stream);
 
 /*
  * Deterministic verification, part 2 (Sections 3 and 4.1): an edge p -> i is accepted iff tokens[i] equals

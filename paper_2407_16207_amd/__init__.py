@@ -23,7 +23,7 @@ GSD_MAX_NODES_PER_SEQ = 512
 GSD_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ("gsd_status_string", "gsd_last_error", "gsd_version", "gsd_build_mask", "gsd_dag_attention_workspace",
-           "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_dag_attention_static", "gsd_node_argmax", "gsd_accept_longest_path",
+           "gsd_dag_attention_splits", "gsd_dag_attention", "gsd_dag_attention_static", "gsd_node_argmax", "gsd_node_argmax_stats", "gsd_accept_longest_path",
            "gsd_unmerge_to_tree", "gsd_gather_rows", "gsd_commit_kv", "gsd_softmax_stats", "gsd_accept_stochastic",
            "gsd_build_token_graph")
 
@@ -100,6 +100,7 @@ def load_library() -> ctypes.CDLL:
         i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
         lib.gsd_build_mask.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp]
         lib.gsd_node_argmax.argtypes = [i32, i32, ctypes.c_int, vp, i64, vp, vp]
+        lib.gsd_node_argmax_stats.argtypes = [i32, i32, ctypes.c_int, vp, i64, vp, vp, vp, vp]
         lib.gsd_accept_longest_path.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, ctypes.c_int, i32, i64, vp, vp,
                                                 vp, vp, vp, vp]
         lib.gsd_unmerge_to_tree.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -264,6 +265,24 @@ def gsd_node_argmax(logits, pred=None, stream=None):
     _check(load_library().gsd_node_argmax(rows, vocab, _dtype_code(logits), _ptr(logits), logits.stride(0),
                                           _ptr(pred), _stream_ptr(stream)))
     return pred
+
+
+def gsd_node_argmax_stats(logits, pred=None, row_max=None, row_sumexp=None, stream=None):
+    """One pass over the logits: (pred, row_max, row_sumexp) as gsd_node_argmax and gsd_softmax_stats give them.
+    See gsd_node_argmax_stats in gsd.h."""
+    import torch
+    if not logits.is_cuda or logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be a GPU tensor [rows, vocab] with a contiguous last dim")
+    rows, vocab = logits.shape
+    pred = torch.empty(rows, dtype=torch.int32, device=logits.device) if pred is None else pred
+    row_max = torch.empty(rows, dtype=torch.float32, device=logits.device) if row_max is None else row_max
+    row_sumexp = torch.empty(rows, dtype=torch.float32, device=logits.device) if row_sumexp is None else row_sumexp
+    _require(pred, torch.int32, "pred")
+    _require(row_max, torch.float32, "row_max")
+    _require(row_sumexp, torch.float32, "row_sumexp")
+    _check(load_library().gsd_node_argmax_stats(rows, vocab, _dtype_code(logits), _ptr(logits), logits.stride(0),
+                                                _ptr(pred), _ptr(row_max), _ptr(row_sumexp), _stream_ptr(stream)))
+    return pred, row_max, row_sumexp
 
 
 def gsd_accept_longest_path(node_offsets, parent_offsets, parent_idx, tokens, root_pred, max_nodes: int,

@@ -70,20 +70,29 @@ __global__ __launch_bounds__(THREADS) void softmax_stats_kernel(int32_t vocab, c
         add_batch(&x, 1);
     }
     const u32x4 *vec = reinterpret_cast<const u32x4 *>(row_ptr + size_t(head) * ELT);
-    for (int c = threadIdx.x; c < nvec; c += THREADS) {
-        const u32x4 w = __builtin_nontemporal_load(vec + c);
-        float x[PER_VEC];
-        if (BF16) {
+    // kBatch loads are issued before the first of them is looked at (one load per lane in flight streams at the pace of
+    // memory latency, not bandwidth); a slot past the end of the row reads the last chunk again and is ignored
+    constexpr int kBatch = 8;
+    for (int c0 = threadIdx.x; c0 < nvec; c0 += THREADS * kBatch) {
+        u32x4 w[kBatch];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                x[2 * j] = __uint_as_float(w[j] << 16);
-                x[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+        for (int u = 0; u < kBatch; ++u) w[u] = __builtin_nontemporal_load(vec + min(c0 + u * THREADS, nvec - 1));
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            if (c0 + u * THREADS >= nvec) break;
+            float x[PER_VEC];
+            if (BF16) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    x[2 * j] = __uint_as_float(w[u][j] << 16);
+                    x[2 * j + 1] = __uint_as_float(w[u][j] & 0xffff0000u);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(w[u][j]);
             }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) x[j] = __uint_as_float(w[j]);
+            add_batch(x, PER_VEC);
         }
-        add_batch(x, PER_VEC);
     }
     {
         const int i = tail_start + threadIdx.x;

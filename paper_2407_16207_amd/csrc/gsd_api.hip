@@ -185,8 +185,22 @@ int gsd_node_argmax(int32_t rows, int32_t vocab, int dtype, const void *logits, 
     if (row_stride < vocab) return fail(GSD_ERR_INVALID_ARG, "row_stride %lld < vocab %d", (long long)row_stride, vocab);
     const uintptr_t elt = dtype == GSD_BF16 ? 2 : 4;
     if (reinterpret_cast<uintptr_t>(logits) % elt != 0) return fail(GSD_ERR_INVALID_ARG, "logits misaligned");
-    hipError_t err = gsd::launch_node_argmax(rows, vocab, dtype, logits, row_stride, pred, (hipStream_t)hip_stream);
+    hipError_t err = gsd::launch_node_argmax(rows, vocab, dtype, logits, row_stride, pred, nullptr, nullptr,
+                                             (hipStream_t)hip_stream);
     return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_node_argmax launch");
+}
+
+int gsd_node_argmax_stats(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
+                          int32_t *pred, float *row_max, float *row_sumexp, void *hip_stream) {
+    if (rows < 1 || vocab < 1) return fail(GSD_ERR_INVALID_ARG, "rows and vocab must be >= 1");
+    if (dtype != GSD_F32 && dtype != GSD_BF16) return fail(GSD_ERR_UNSUPPORTED, "dtype %d", dtype);
+    if (!logits || !pred || !row_max || !row_sumexp) return fail(GSD_ERR_INVALID_ARG, "NULL pointer argument");
+    if (row_stride < vocab) return fail(GSD_ERR_INVALID_ARG, "row_stride %lld < vocab %d", (long long)row_stride, vocab);
+    const uintptr_t elt = dtype == GSD_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(logits) % elt != 0) return fail(GSD_ERR_INVALID_ARG, "logits misaligned");
+    hipError_t err = gsd::launch_node_argmax(rows, vocab, dtype, logits, row_stride, pred, row_max, row_sumexp,
+                                             (hipStream_t)hip_stream);
+    return err == hipSuccess ? GSD_OK : hip_fail(err, "gsd_node_argmax_stats launch");
 }
 
 int gsd_accept_longest_path(int32_t batch, int32_t total_nodes, int32_t max_nodes, const int32_t *node_offsets,

@@ -12,8 +12,9 @@ hipError_t launch_build_mask(int32_t batch, int32_t max_nodes, int32_t words_per
                              const int32_t *parent_offsets, const int32_t *parent_idx, uint64_t *mask,
                              int32_t *dag_error_flag, hipStream_t stream);
 
+// row_max / row_sumexp: both NULL (argmax only) or both given (the same sweep also leaves the softmax normalisers)
 hipError_t launch_node_argmax(int32_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
-                              int32_t *pred, hipStream_t stream);
+                              int32_t *pred, float *row_max, float *row_sumexp, hipStream_t stream);
 
 hipError_t launch_accept(int32_t batch, int32_t max_nodes, const int32_t *node_offsets,
                          const int32_t *parent_offsets, const int32_t *parent_idx, const int32_t *tokens,

@@ -141,6 +141,10 @@ def test_stochastic_entry_points_validate(lib):
     p = ctypes.c_void_p(0x10000)
     null = ctypes.c_void_p(0)
     assert lib.gsd_softmax_stats(0, 10, 0, p, 10, p, p, null) == gsd.GSD_ERR_INVALID_ARG
+    assert lib.gsd_node_argmax_stats(0, 10, 0, p, 10, p, p, p, null) == gsd.GSD_ERR_INVALID_ARG
+    assert lib.gsd_node_argmax_stats(4, 10, 0, p, 10, p, null, p, null) == gsd.GSD_ERR_INVALID_ARG
+    assert lib.gsd_node_argmax_stats(4, 10, 7, p, 10, p, p, p, null) == gsd.GSD_ERR_UNSUPPORTED
+    assert lib.gsd_node_argmax_stats(4, 10, 1, p, 9, p, p, p, null) == gsd.GSD_ERR_INVALID_ARG
     assert lib.gsd_softmax_stats(4, 10, 0, p, 9, p, p, null) == gsd.GSD_ERR_INVALID_ARG
     assert lib.gsd_softmax_stats(4, 10, 3, p, 10, p, p, null) == gsd.GSD_ERR_UNSUPPORTED
     assert lib.gsd_softmax_stats(4, 10, 0, p, 10, null, p, null) == gsd.GSD_ERR_INVALID_ARG

@@ -387,6 +387,44 @@ def test_build_token_graph_matches_oracle(gpu, tau, theta_prob, theta_sib):
     assert rflag == 0 and np.array_equal(gpu.mask_to_numpy(mask), rmask)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_argmax_and_softmax_normalisers_in_one_pass(gpu, ref, dtype):
+    """gsd_node_argmax_stats: the argmax bit-exact against the oracle, the normalisers against the fp64 softmax, on
+    aligned and misaligned rows, ties, -inf rows and the full config-4 logits (the launch the benchmark times)."""
+    import paper_2407_16207_amd as gsd
+    from paper_2407_16207_amd.workload import f32_to_bf16_bits, bf16_bits_to_f32, make_workload
+    rng = np.random.default_rng(77)
+    for vocab in (1, 7, 1000, 32003):
+        x = (rng.standard_normal((9, vocab)) * 3).astype(np.float32)
+        x[0, :] = 0.5
+        x[1, vocab - 1] = 9.0
+        x[2, 0] = 9.0
+        x[3, :] = -np.inf
+        if vocab > 10:
+            x[6, [vocab - 2, 5, vocab // 2]] = 7.0
+        stored = x if dtype == "f32" else f32_to_bf16_bits(x)
+        vals = x if dtype == "f32" else bf16_bits_to_f32(stored)
+        t = gpu.to_dev(stored)
+        for view, np_view in ((t, vals), (t[:, 1:], vals[:, 1:])) if vocab > 1 else ((t, vals),):
+            pred, m, s_ = gsd.gsd_node_argmax_stats(view)
+            torch.cuda.synchronize()
+            assert np.array_equal(pred.cpu().numpy(), ref.node_argmax(np.ascontiguousarray(np_view)))
+            _, m_ref, z_ref = gsd_next.softmax_rows(np_view.astype(np.float64))
+            assert np.array_equal(m.cpu().numpy().astype(np.float64), m_ref)
+            got = s_.cpu().numpy().astype(np.float64)
+            ok = z_ref > 0
+            assert np.abs(got[ok] / z_ref[ok] - 1).max() < 2e-6 and np.all(got[~ok] == 0)
+    if dtype == "bf16":
+        w = make_workload(4, with_qkv=False)
+        logits = gpu.to_dev(w.logits)
+        pred, m, s_ = gsd.gsd_node_argmax_stats(logits)
+        torch.cuda.synchronize()
+        assert np.array_equal(pred.cpu().numpy(), ref.node_argmax(w.logits))
+        assert torch.equal(pred, gsd.gsd_node_argmax(logits))
+        m2, s2 = gsd.gsd_softmax_stats(logits)
+        assert torch.equal(m, m2) and (s_ / s2 - 1).abs().max().item() < 2e-6
+
+
 def compare_graph_with_oracle(gpu, node_offsets, par, tok, q, tau, theta_prob, theta_sib, max_nodes=512):
     import paper_2407_16207_amd as gsd
     flag = torch.zeros(1, dtype=torch.int32, device="cuda")
