@@ -160,6 +160,16 @@ def bench_commit_kv(gsd, w, d_kv_offsets, d_prefix_lens, accept_len, accept_path
                                                            d_prefix_lens, d_len, d_path, new_prefix_lens=new_len),
                        reps)
     res["full_depth_acceptance"] = summary(ms, deep_len, deep_path)
+    # what this chip does on a plain device-to-device copy of the same volume (as many bytes read and as many written,
+    # sources and destinations rotated like the caches): the practical ceiling for a kernel that reads and writes alike
+    vol = int(res["full_depth_acceptance"]["algorithmic_bytes_per_launch"] // 2)
+    del caches
+    srcs = [torch.empty(vol, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    dsts = [torch.empty(vol, dtype=torch.uint8, device="cuda") for _ in range(4)]
+    ms = time_launches(stream, lambda i: dsts[i % 4].copy_(srcs[i % 4]), reps)
+    res["plain_copy_same_volume"] = {"bytes_read_plus_written": 2.0 * vol, "avg_launch_ms": ms,
+                                     "achieved": 2.0 * vol / (ms * 1e-3) / 1e9, "unit": "GB/s",
+                                     "frac": 2.0 * vol / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
     return res
 
 
@@ -421,9 +431,14 @@ def main():
     ap.add_argument("--cpu-sample-nodes", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next", action="store_true", help="skip the un-merge and KV-commit measurements")
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
+                    help="2 (default): the argmax + acceptance call runs on a second stream of the same priority next to "
+                         "mask + attention, forked at the start of every step and joined at its end; 1: all on one stream")
+    ap.add_argument("--no-config5", action="store_true", help="skip the config-5 graph-against-tree attention leg")
     ap.add_argument("--cache-layers", type=int, default=80, help="depth of the KV cache the commit step is timed on")
     ap.add_argument("--splits", type=int, default=0, help="force the attention KV split count (0 = library's choice)")
-    ap.add_argument("--profile-stage", choices=["attention", "argmax", "mask", "accept", "copy"], default=None,
+    ap.add_argument("--profile-stage", choices=["attention", "argmax", "argmax_stats", "mask", "accept", "copy"],
+                    default=None,
                     help="profiling aid: launch only this stage --steps times (after one full step) and print a "
                          "short JSON line; 'copy' runs a plain 256 MiB device copy for counter calibration")
     args = ap.parse_args()
@@ -487,6 +502,33 @@ def main():
         if events:
             events[3].record(stream)
 
+    side = torch.cuda.Stream()                # default priority, like the main stream
+
+    def step_two_streams():
+        """The same three calls; the vocabulary sweep and the acceptance (which need neither the mask nor the
+        attention output) go to a second stream.  The fork at the start and the join at the end keep steps apart:
+        nothing of step s+1 starts before everything of step s has finished."""
+        side.wait_stream(stream)
+        gsd.gsd_build_mask(node_offsets, parent_offsets, parent_idx, N, words_per_row=W, mask=mask)
+        with torch.cuda.stream(side):
+            gsd.gsd_accept_longest_path(node_offsets, parent_offsets, parent_idx, tokens, root_pred, N, logits=logits,
+                                        pred=pred, accept_len=accept_len, accept_path=accept_path, bonus_token=bonus)
+        gsd.gsd_dag_attention_desc(desc)
+        stream.wait_stream(side)
+
+    def timed_pass(fn):
+        for _ in range(args.warmup):
+            fn()
+        e_a, e_b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t_a = time.perf_counter()
+        e_a.record(stream)
+        for _ in range(args.steps):
+            fn()
+        e_b.record(stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_a) * 1e3 / args.steps, e_a.elapsed_time(e_b) / args.steps
+
     if args.profile_stage:
         step()
         torch.cuda.synchronize()
@@ -495,6 +537,7 @@ def main():
         launch = {
             "attention": lambda: gsd.gsd_dag_attention_desc(desc),
             "argmax": lambda: gsd.gsd_node_argmax(logits, pred=pred),
+            "argmax_stats": lambda: gsd.gsd_node_argmax_stats(logits, pred=pred),
             "mask": lambda: gsd.gsd_build_mask(node_offsets, parent_offsets, parent_idx, N, words_per_row=W, mask=mask),
             "accept": lambda: gsd.gsd_accept_longest_path(node_offsets, parent_offsets, parent_idx, tokens, root_pred,
                                                           N, pred=pred, accept_len=accept_len,
@@ -514,25 +557,14 @@ def main():
                           "copy_bytes": (256 << 20) if src is not None else None}), flush=True)
         return
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    # The timed region: exactly K steps, nothing but the step's own launches on the stream (one HIP event before the
-    # first and one after the last).  Events between the launches of a step cost 13 us per step here (0.293 ms
-    # without, 0.306 ms with four), so the per-stage times and the attention kernel's launch duration come from a
-    # second, identical pass of K steps that carries them.
-    e_first, e_last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e_first.record(stream)
-    for s in range(args.steps):
-        step()
-    e_last.record(stream)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-    ms_per_step_events = e_first.elapsed_time(e_last) / args.steps
+    # The timed region: W warm-up steps, then exactly K steps with nothing but the steps' own launches (and, with two
+    # streams, the fork and join of each step) between two synchronisations.  Events between the launches of a step
+    # cost 13 us per step here (0.293 ms without, 0.306 ms with four), so the per-stage times and the attention kernel's
+    # launch duration come from a further, single-stream pass of K steps that carries them.  Both schedules are timed;
+    # the headline is the one --streams names.
+    one_ms, one_ms_events = timed_pass(step)
+    two_ms, two_ms_events = timed_pass(step_two_streams)
+    ms_per_step, ms_per_step_events = (two_ms, two_ms_events) if args.streams == 2 else (one_ms, one_ms_events)
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -639,6 +671,9 @@ def main():
         "attention_tflops": attn_tflops,
         "attention_pct_bf16_mfma_peak": 100.0 * attn_tflops / MFMA_BF16_PEAK_TFLOPS,
         "ms_per_step_by_hip_events": ms_per_step_events,
+        "schedule": {"streams": args.streams, "ms_per_step_one_stream": one_ms, "ms_per_step_two_streams": two_ms,
+                     "note": "two streams: mask + attention on one, argmax + acceptance on the other (same priority), "
+                             "forked and joined inside every step"},
         "stage_ms": {"mask": float(mask_ms), "attention": float(attn_ms), "argmax_plus_accept": float(accept_ms),
                      "argmax_alone": float(argmax_ms), "ms_per_step_of_this_pass": ms_per_step_staged,
                      "note": "second pass of the same K steps with a HIP event between the launches (the events "
@@ -662,7 +697,7 @@ def main():
         result["unmerge_to_tree"] = bench_unmerge(gsd, w, dev, stream)
         result["stochastic_verify"] = bench_stochastic(gsd, w, dev, logits, stream)
         result["build_token_graph"] = bench_build_graph(gsd, w, dev, stream)
-        if cfg.name.startswith("cfg4"):
+        if cfg.name.startswith("cfg4") and not args.no_config5:
             result["config5_dag_vs_tree"] = bench_config5_dag_vs_tree(gsd, dev)
         result["matrix_pipe_sustained"] = bench_matrix_pipe(gsd, w, q, k, v, kv_offsets, prefix_lens, node_offsets,
                                                             mask, out, workspace, need, flops, stream, args.splits)
