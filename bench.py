@@ -560,10 +560,10 @@ def main():
     # The timed region: W warm-up steps, then exactly K steps with nothing but the steps' own launches (and, with two
     # streams, the fork and join of each step) between two synchronisations.  Events between the launches of a step
     # cost 13 us per step here (0.293 ms without, 0.306 ms with four), so the per-stage times and the attention kernel's
-    # launch duration come from a further, single-stream pass of K steps that carries them.  Both schedules are timed;
-    # the headline is the one --streams names.
+    # launch duration come from a further, single-stream pass of K steps that carries them.  With --streams 2 both schedules
+    # are timed and the headline is the two-stream one; --streams 1 runs the one-stream schedule only.
     one_ms, one_ms_events = timed_pass(step)
-    two_ms, two_ms_events = timed_pass(step_two_streams)
+    two_ms, two_ms_events = timed_pass(step_two_streams) if args.streams == 2 else (None, None)   # --streams 1: never run
     ms_per_step, ms_per_step_events = (two_ms, two_ms_events) if args.streams == 2 else (one_ms, one_ms_events)
 
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
