@@ -522,8 +522,14 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     // The same one score at a time, for the loop: the vector work is dealt out evenly, one score behind every matrix
     // instruction (an even score waits in x_hold for its odd neighbour, with which it is packed).
     float x_hold[RBW];
-    auto convert_one = [&](floatx16 (&sc)[2], int e, float &sum, int rb) __attribute__((always_inline)) {
-        const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e / 16][e % 16], c_log2, nm[rb]));
+    // Split in two so that nothing waits for an exponential: score e is started (multiply-add, exp2) in one slice
+    // and retired (added to the sum, packed with its neighbour) in the slice that starts score e+1.
+    float x_new[RBW];
+    auto start_one = [&](floatx16 (&sc)[2], int e, int rb) __attribute__((always_inline)) {
+        x_new[rb] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e / 16][e % 16], c_log2, nm[rb]));
+    };
+    auto retire_one = [&](int e, float &sum, int rb) __attribute__((always_inline)) {
+        const float x = x_new[rb];
         sum += x;
         asm volatile("" : "+v"(sum));
         if (e & 1) {
@@ -577,7 +583,10 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 }
 #pragma unroll
                 for (int u = 0; u < 32 - B_SCORES; ++u)            // score B_SCORES + u goes into slice u*NQK/(32-B_SCORES)
-                    if ((u * NQK) / (32 - B_SCORES) == idx) convert_one(sc[rb], B_SCORES + u, sum[rb], rb);
+                    if ((u * NQK) / (32 - B_SCORES) == idx) {
+                        if (u > 0) retire_one(B_SCORES + u - 1, sum[rb], rb);
+                        start_one(sc[rb], B_SCORES + u, rb);
+                    }
                 GSD_SLICE_END();
             }
         }
@@ -585,6 +594,8 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
         // phase B, behind the barrier, and the overlap with the matrix pipe is lost
         float tot[RBW];
         bool trip = false;
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb) retire_one(31, sum[rb], rb);
 #pragma unroll
         for (int rb = 0; rb < RBW; ++rb) {
             asm volatile("" : "+v"(pf[rb][1]), "+v"(pf[rb][2]), "+v"(pf[rb][3]), "+v"(sum[rb]));
@@ -669,13 +680,17 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
                 if (HAS_NEXT) {
 #pragma unroll
                     for (int u = 0; u < B_SCORES; ++u)             // score u goes into slice CONV_FIRST + u*(NPV-CONV_FIRST)/B_SCORES
-                        if (CONV_FIRST + (u * (NPV - CONV_FIRST)) / B_SCORES == idx)
-                            convert_one(s_next[rb], u, sum[rb], rb);
+                        if (CONV_FIRST + (u * (NPV - CONV_FIRST)) / B_SCORES == idx) {
+                            if (u > 0) retire_one(u - 1, sum[rb], rb);
+                            start_one(s_next[rb], u, rb);
+                        }
                 }
                 GSD_SLICE_END();
             }
         }
         if (HAS_NEXT) {
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb) retire_one(B_SCORES - 1, sum[rb], rb);
 #pragma unroll
             for (int rb = 0; rb < RBW; ++rb) {
                 asm volatile("" : "+v"(pf[rb][0]), "+v"(pf[rb][1]), "+v"(sum[rb]));
