@@ -43,6 +43,18 @@ def test_equals_library_sdpa_with_expanded_mask(ref, cfg):
     np.testing.assert_allclose(out, sdpa_reference(w, mask), rtol=0, atol=1e-12)
 
 
+def test_peaked_scores_against_library_sdpa(ref):
+    """Scores of several hundred (a softmax scale 200 times the usual one): the oracle's max subtraction must hold where
+    exp of a raw score overflows fp64 and most keys underflow against the largest one."""
+    w = make_workload(SMALL, seed=11)
+    w.softmax_scale *= 200.0
+    mask, _ = ref.build_mask(w.node_offsets, w.parent_offsets, w.parent_idx)
+    out, lse = ref.dag_attention(w.q, w.k, w.v, w.kv_offsets, w.prefix_lens, w.node_offsets, mask, w.softmax_scale,
+                                 return_lse=True)
+    assert np.abs(lse).max() > 710.0 and np.isfinite(out).all() and np.isfinite(lse).all()
+    np.testing.assert_allclose(out, sdpa_reference(w, mask), rtol=0, atol=1e-12)
+
+
 def test_chain_is_causal_attention(ref):
     """A chain-shaped graph (plain sequence-structured drafting, Section 3) must reduce to ordinary causal
     attention over [prefix ; draft], read off at the last n positions."""
