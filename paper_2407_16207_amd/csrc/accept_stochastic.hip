@@ -382,7 +382,7 @@ __global__ __launch_bounds__(kResampleThreads) void resample_kernel(const gsd_st
         part[threadIdx.x] = local;
         __syncthreads();
         for (int dd = 1; dd < kResampleThreads; dd <<= 1) {      // inclusive scan
-            const float add = threadIdx.x >= dd ? part[threadIdx.x - dd] : 0.f;
+            const float add = int(threadIdx.x) >= dd ? part[threadIdx.x - dd] : 0.f;
             __syncthreads();
             part[threadIdx.x] += add;
             __syncthreads();

@@ -458,7 +458,7 @@ __global__ __launch_bounds__(NW * 64, RBW == 2 ? 1 : 8 / NW) void dag_attention_
     auto adjust = [&](float tot, int rb) __attribute__((always_inline)) {
         const bool bad_here = !(tot < kSumPoison);
         const auto sw = __builtin_amdgcn_permlane32_swap(uint32_t(bad_here), uint32_t(bad_here), false, false);
-        poison[rb] = poison[rb] | (sw[0] | sw[1]) != 0;
+        poison[rb] = poison[rb] | ((sw[0] | sw[1]) != 0);
         const float big = max_across_halves(bad_here ? 0.f : tot);
         const float delta = big < kSumRaise ? 0.f : float(__builtin_amdgcn_frexp_expf(big));   // big < 2^delta
         const float alpha = __builtin_amdgcn_exp2f(-delta);                                    // exact, 1 if nothing moves
@@ -988,7 +988,6 @@ static WgShape shape_of(const gsd_attn_desc &d) {
     const int group = d.num_q_heads / d.num_kv_heads;
     return d.max_nodes * group >= 256 ? WgShape{8, 1} : WgShape{4, 1};
 }
-static int waves_of(const gsd_attn_desc &d) { return shape_of(d).waves; }
 
 static int q_tiles_of(const gsd_attn_desc &d) {
     const int group = d.num_q_heads / d.num_kv_heads;

@@ -3,10 +3,11 @@
 // Paper Section 4.1 lets a flattened token attend only to its ancestors; on the merged graph of Section 5.3
 // that set is the closure over all parent edges.  Rows live in LDS as packed 64-bit words and are relaxed
 //     row[i] <- bit(i) | OR_{p in parents(i)} row[p]
-// level by level: a node takes its parents' rows once they are final.  Nodes are in topological order, so this
-// ends after depth+1 sweeps; the loop is also hard-bounded by the node count, so every wave leaves the kernel.  One thread per node holds the node's whole row (W words) and its first four
-// parent ids in registers; a sweep is four narrow LDS reads (are my parents final?), the wide reads of the
-// parents' rows once per node, and one barrier of a work-group as large as the sequence.
+// in data-flow order: a node takes its parents' rows as soon as they are final and publishes its own with a flag;
+// every wavefront polls the flags of its own nodes' parents, no work-group barrier inside the loop.  Nodes are in
+// topological order, so the lowest unfinished node is always ready, and the loop is bounded on top of that, so every
+// wave leaves the kernel.  One thread per node holds the node's whole row (W words) and its first four parent ids in
+// registers; a poll is four narrow LDS reads (are my parents final?), then, once, the wide reads of the parents' rows.
 #include "gsd_internal.h"
 
 namespace gsd {
@@ -22,7 +23,6 @@ __global__ __launch_bounds__(GSD_MAX_NODES_PER_SEQ) void build_mask_kernel(
     __shared__ int32_t edge_cache[kEdgeCacheInts];
     __shared__ int32_t off_cache[GSD_MAX_NODES_PER_SEQ + 1];
     __shared__ int32_t done_at[GSD_MAX_NODES_PER_SEQ + 1];
-    __shared__ int changed_flag[3];
 
     const int b = blockIdx.x;
     const int threads = blockDim.x;                          // >= max_nodes: one node per thread
@@ -41,7 +41,6 @@ __global__ __launch_bounds__(GSD_MAX_NODES_PER_SEQ) void build_mask_kernel(
     for (int i = threadIdx.x; i <= n; i += threads) off_cache[i] = parent_offsets[base + i] - e0;
     if (cached)
         for (int e = threadIdx.x; e < e1 - e0; e += threads) edge_cache[e] = parent_idx[e0 + e];
-    if (threadIdx.x < 3) changed_flag[threadIdx.x] = 0;
     __syncthreads();
 
     const int i = threadIdx.x;
@@ -82,33 +81,37 @@ __global__ __launch_bounds__(GSD_MAX_NODES_PER_SEQ) void build_mask_kernel(
             r[w] = (w == (i >> 6)) ? (uint64_t(1) << (i & 63)) : uint64_t(0);
             rows[i * W + w] = r[w];
         }
-        done_at[i] = 0x7fffffff;
+        done_at[i] = 0;
     }
-    if (threadIdx.x == 0) done_at[n] = -1;
+    if (threadIdx.x == 0) done_at[n] = 1;
     __syncthreads();
     const bool more = active && e_hi - e_lo > kRegParents;     // rare: a node with more than four parents
 
-    // Level-synchronous: a node takes its parents' rows once, in the first sweep that finds all of them final
-    // (done_at[p] = sweep in which row p became final, compared against the current sweep so that only rows
-    // finished before the last barrier count), and is final itself from then on.  Sweep s finishes the nodes at
-    // depth s; the others spend four narrow LDS reads.  Nodes are in topological order, so the lowest unfinished
-    // node is always ready: a sweep that finishes nothing means everything is finished.  That is signalled through
-    // three rotating LDS flags: set in sweep s, read after its barrier, cleared during sweep s+1 for sweep s+2.
+    // Data flow instead of sweeps with barriers: a node takes its parents' rows as soon as all of them are final
+    // (done_at[p] != 0, published after the row itself; LDS operations of a wave complete in order), and is final
+    // itself from then on.  Every wave polls on its own; the wavefronts of a work-group are all resident, nodes are in
+    // topological order and only earlier nodes are ever waited for, so the lowest unfinished node is always ready and
+    // every poll of its wave finishes it: the loop ends after at most depth+1 productive polls per wave.  It is bounded
+    // all the same (kPollLimit polls; a wave that hits the bound reports the graph as bad and writes what it has).
+    auto is_final = [&](int node) -> bool {     // relaxed LDS read that the compiler may neither cache nor drop
+        return __hip_atomic_load(&done_at[node], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) != 0;
+    };
     bool mine_done = !active;
-    for (int sweep = 0; sweep <= n; ++sweep) {
-        bool finished = false;
+    constexpr int kPollLimit = 1 << 16;
+    for (int poll = 0; poll < kPollLimit; ++poll) {
         if (!mine_done) {
             bool ready = true;
 #pragma unroll
-            for (int x = 0; x < kRegParents; ++x) ready &= done_at[par_done[x]] < sweep;
+            for (int x = 0; x < kRegParents; ++x) ready &= is_final(par_done[x]);
             if (more) {
                 for (int e = e_lo + kRegParents; e < e_hi; ++e) {
                     const int pp = edge_at(e);
-                    if (pp >= 0 && pp < i) ready &= done_at[pp] < sweep;
+                    if (pp >= 0 && pp < i) ready &= is_final(pp);
                     else if (pp != -1) bad = true;
                 }
             }
             if (ready) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");     // the rows are read after their flags
 #pragma unroll
                 for (int x = 0; x < kRegParents; ++x)
 #pragma unroll
@@ -124,17 +127,13 @@ __global__ __launch_bounds__(GSD_MAX_NODES_PER_SEQ) void build_mask_kernel(
                 }
 #pragma unroll
                 for (int w = 0; w < W; ++w) rows[i * W + w] = r[w];
-                done_at[i] = sweep;
+                __hip_atomic_store(&done_at[i], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);   // after the row
                 mine_done = true;
-                finished = true;
             }
         }
-        const int slot = sweep % 3;
-        if (finished) changed_flag[slot] = 1;
-        if (threadIdx.x == 0) changed_flag[(sweep + 1) % 3] = 0;
-        __syncthreads();
-        if (changed_flag[slot] == 0) break;       // uniform: everybody reads the same flag after the barrier
+        if (__all(mine_done)) break;              // wave-uniform
     }
+    if (!mine_done) bad = true;                   // poll limit reached (never, with the guarantees above)
 
     if (active) {
         uint64_t *out = mask + (base + i) * words_per_row;
