@@ -5,22 +5,25 @@
 // which depends on which EARLIER nodes exist: the construction is sequential across layers, so the work-group walks
 // the tree layer by layer (nodes come breadth first: a layer is a run of consecutive ids).  Within a layer everything
 // is parallel: existence comes from the layer above, and the first occurrence of a node's tau-gram is a lookup.
-// Before the walk every node gets the exact equivalence class of its tau-gram among ALL tree nodes (no hashing):
-// class_t(i) = the smallest j <= i with tok[j] == tok[i] and class_(t-1)(parent j) == class_(t-1)(parent i), built
-// level by level with one all-pairs comparison per level (the candidates of a wave sit one per lane and are
-// broadcast with readlane, so the comparison touches no memory).  During the walk the smallest existing node of
-// every class is kept in a table (atomic min by the layer's existing nodes), so "the earliest existing earlier node
-// with the same tau-gram" is one read.
+// Before the walk every node gets the exact equivalence class of its tau-gram among ALL tree nodes:
+// class_t(i) = the smallest j with tok[j] == tok[i] and class_(t-1)(parent j) == class_(t-1)(parent i), built level
+// by level through an open-addressed table in LDS whose slots hold the full 64-bit key (token, class of the parent
+// one level down), so two nodes share a slot only if their keys are equal: hashing picks where to look, never what
+// is equal, and the smallest id of a slot does not depend on the order of arrival.  During the walk the smallest
+// existing node of every class is kept in a table (atomic min by the layer's existing nodes), so "the earliest
+// existing earlier node with the same tau-gram" is one read.
 //
 // Merging (Section 5.3: an edge from the redundant node R to the first occurrence F of its tau-gram, so that what
 // follows F is reused below R) makes R one more parent of every child of F, unless R already descends from F in the
 // graph built so far: that would close a cycle, and R then stays a bare leaf.  Which nodes exist does not depend on
 // these decisions, but the decisions depend on each other in generation order (an edge drawn for one node changes
-// who descends from whom for the next), so after the walk the redundant nodes are taken one at a time, in id order,
-// against per-node ancestor bit rows in LDS: one bit test, then every descendant of F takes over R's ancestors, one
-// barrier per redundant node.  An edge from a later layer into an earlier one breaks the generation order as a
-// topological order: the fill kernel renumbers the graph by level (longest distance from the root, by relaxation),
-// nodes of one level in generation order.
+// who descends from whom for the next), so after the walk the redundant nodes are taken one at a time, in id order.
+// The decisions only ever ask whether one node's first occurrence is an ancestor of another redundant node, so one
+// wave keeps exactly those bits in registers (a row per redundant node, a column per pair) and runs the whole
+// sequence with lane broadcasts, no LDS traffic and no barrier in between.
+// An edge from a later layer into an earlier one breaks the generation order as a topological order: the fill kernel
+// renumbers the graph by level (longest distance from the root, by relaxation), nodes of one level in generation
+// order (a counting sort: ballots within a wave, one scan over the per-wave counts).
 // Two launches: the first only counts nodes and edges per sequence, the second repeats the construction and writes
 // the packed graph behind the sequences before it (the library keeps no scratch memory).
 #include "gsd_internal.h"
@@ -41,7 +44,10 @@ struct GraphLds {
     int32_t cls[GSD_MAX_NODES_PER_SEQ];        // class of the node's tau-gram (an earlier-or-equal node id), -1 if none
     int32_t first_ex[GSD_MAX_NODES_PER_SEQ];   // per class: smallest existing node seen so far
     int32_t merge_cnt[GSD_MAX_NODES_PER_SEQ];  // nodes merged into this one (merge edges actually drawn)
-    uint64_t anc[GSD_MAX_NODES_PER_SEQ * 8];   // ancestor bit row of every node in the graph built so far (itself included)
+    // 32 KB used three times over: the key table of the tau-gram classes, then (merge decisions) per node the set of
+    // redundant nodes it is the first occurrence for, word-major, then the counting tables of the renumbering
+    uint64_t anc[GSD_MAX_NODES_PER_SEQ * 8];
+    int32_t wave_tot[16];
     int32_t bad;
     int32_t max_depth;
 };
@@ -50,7 +56,7 @@ constexpr int kFlagMerged = 0x200;             // redundant node whose merge edg
 
 // Runs the construction for the calling work-group's sequence; afterwards flags (bit8 = exists), merged_to and depth
 // are final.  Returns the node count through n_out.
-__device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__restrict__ tree_parent,
+__device__ __forceinline__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__restrict__ tree_parent,
                           const int32_t *__restrict__ tokens, const float *__restrict__ draft_prob, int tau,
                           float theta_prob, float theta_sib) {
     const int i = threadIdx.x;
@@ -81,19 +87,17 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
         if (p >= -1) atomicMax(&s.sib_max[p + 1], __float_as_uint(fmaxf(s.q[i], 0.f)));
     }
     __syncthreads();
-    // depths by relaxation (a chain can be as long as the sequence)
-    for (int sweep = 0; sweep <= n; ++sweep) {
-        int changed = 0;
-        if (i < n && s.depth[i] == 0) {
-            const int p = s.par[i];
-            const int d = p == -1 ? 1 : (p >= 0 && s.depth[p] > 0 ? s.depth[p] + 1 : 0);
-            if (d > 0) {
-                s.depth[i] = d;
-                changed = 1;
-            }
+    // depth = nodes on the way up to the root; a parent is an earlier node, so the walk ends within i + 1 steps, and
+    // a node that hangs off a malformed one never reaches the root and keeps depth 0
+    if (i < n) {
+        int d = 0, a = i;
+        while (a >= 0) {
+            ++d;
+            a = s.par[a];
         }
-        if (!__syncthreads_or(changed)) break;
+        s.depth[i] = a == -1 ? d : 0;
     }
+    __syncthreads();
     if (i < n) {
         if (i > 0 && s.depth[i] < s.depth[i - 1]) s.bad = 1;       // not breadth first
         atomicMax(&s.max_depth, s.depth[i]);
@@ -103,9 +107,13 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
     const int my_depth = i < n ? s.depth[i] : 0;
 
     // tau-gram classes, level by level.  At level t a node with depth >= t has the key (its token, the level t-1
-    // class of its parent); its class is the smallest node id with the same key.  Wave w holds nodes 64w .. 64w+63
-    // and only ever needs candidates below that, 64 at a time, one per lane.
-    const int lane = i & 63;
+    // class of its parent); its class is the smallest node id with the same key.  The nodes with a key claim a slot
+    // of the table by compare-and-swap on the key itself (linear probing; at most 512 keys in 2048 slots, so a free
+    // slot always turns up) and leave the minimum of their ids there.
+    constexpr int kSlots = 2048;
+    constexpr unsigned long long kEmpty = ~0ull;       // no key looks like this: the low half is a class + 1 <= 512
+    unsigned long long *slot_key = reinterpret_cast<unsigned long long *>(s.anc);
+    int32_t *slot_min = reinterpret_cast<int32_t *>(s.anc + kSlots);
     int my_cls = -1;                                   // class at the level just finished (level 0: everyone alike)
     const int32_t my_tok = i < n ? s.tok[i] : 0;
     const int my_par = i < n ? s.par[i] : -2;
@@ -113,25 +121,31 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
     for (int t = 1; t <= levels; ++t) {
         const int my_prev = t == 1 ? 0 : (my_par >= 0 ? s.cls[my_par] : -1);     // class of the parent one level down
         const bool my_valid = my_depth >= t;
-        s.scan[i] = my_prev;                           // staged so that the candidates can be fetched one per lane
-        __syncthreads();                               // (also: everyone has read the previous level's classes)
-        int found = my_valid ? i : -1;
-        for (int c0 = 0; c0 <= (i | 63) && c0 < n; c0 += 64) {      // uniform per wave
-            const int j = c0 + lane;
-            const int32_t cand_tok = j < n ? s.tok[j] : 0;
-            const int32_t cand_prev = j < n ? s.scan[j] : -1;
-            const int cand_valid = (j < n && s.depth[j] >= t) ? 1 : 0;
-            for (int l = 0; l < 64; ++l) {
-                const int32_t tj = __builtin_amdgcn_readlane(cand_tok, l);
-                const int32_t pj = __builtin_amdgcn_readlane(cand_prev, l);
-                const int vj = __builtin_amdgcn_readlane(cand_valid, l);
-                const int jj = c0 + l;
-                if (my_valid && vj && jj < found && tj == my_tok && pj == my_prev) found = jj;
-            }
+        for (int x = i; x < kSlots; x += kGraphThreads) {
+            slot_key[x] = kEmpty;
+            slot_min[x] = 0x7fffffff;
         }
-        my_cls = found;
+        __syncthreads();                               // (also: everyone has read the previous level's classes)
+        int slot = -1;
+        if (my_valid) {
+            const unsigned long long key = (static_cast<unsigned long long>(static_cast<uint32_t>(my_tok)) << 32) |
+                                           static_cast<uint32_t>(my_prev + 1);
+            uint32_t h = (static_cast<uint32_t>(my_tok) * 0x9E3779B1u) ^ (static_cast<uint32_t>(my_prev + 1) * 0x85EBCA6Bu);
+            h = (h ^ (h >> 15)) & (kSlots - 1);
+            for (int probe = 0; probe < kSlots; ++probe) {
+                const unsigned long long seen = atomicCAS(&slot_key[h], kEmpty, key);
+                if (seen == kEmpty || seen == key) {
+                    slot = int(h);
+                    break;
+                }
+                h = (h + 1) & (kSlots - 1);
+            }
+            if (slot >= 0) atomicMin(&slot_min[slot], i);
+        }
+        __syncthreads();
+        my_cls = slot >= 0 ? slot_min[slot] : -1;
         s.cls[i] = my_cls;
-        __syncthreads();                               // classes of this level published, staging area free again
+        __syncthreads();                               // classes of this level published, table free again
     }
 
     for (int layer = 1; layer <= max_depth; ++layer) {
@@ -164,66 +178,155 @@ __device__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__res
     }
 }
 
-// inclusive scan of `value` over the work-group's threads in LDS; returns this thread's inclusive prefix
-__device__ int block_scan(int32_t *buf, int value) {
-    const int i = threadIdx.x;
-    buf[i] = value;
-    __syncthreads();
-    for (int d = 1; d < kGraphThreads; d <<= 1) {
-        const int add = i >= d ? buf[i - d] : 0;
-        __syncthreads();
-        buf[i] += add;
-        __syncthreads();
+// Inclusive scan of `value` over the work-group's threads: within a wave by shuffles, across waves through the
+// eight wave totals.  Leaves every thread's inclusive prefix in buf[] (published by the closing barrier) and returns
+// the caller's own.
+__device__ __forceinline__ int block_scan(GraphLds &s, int32_t *buf, int value) {
+    const int i = threadIdx.x, lane = i & 63, wave = i >> 6;
+    int v = value;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(v, d, 64);
+        if (lane >= d) v += up;
     }
-    return buf[i];
+    if (lane == 63) s.wave_tot[wave] = v;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kGraphThreads / 64; ++w)
+        if (w < wave) v += s.wave_tot[w];
+    buf[i] = v;
+    __syncthreads();
+    return v;
+}
+
+// The decisions of decide_merges() for n_red <= 64 * NC redundant nodes, taken by one wave without touching LDS in
+// between.  Pair k is the k-th redundant node R_k (in id order) with the first occurrence F_k of its tau-gram.
+// All that the decisions ever look at is whether some F_k is an ancestor of some R_j, so the ancestor sets are kept
+// as one bit per pair: lane j of chunk c holds the row of pair 64 c + j, bit k of it says "F_k is an ancestor of
+// R_j".  Pair k in turn: its own bit k decides (set: R_k descends from F_k, no edges); otherwise every row with bit
+// k set, that is every R below F_k, takes over the row of R_k, handed out with readlane.  Rows of earlier pairs and
+// bits of earlier pairs are never looked at again, so the sweep leaves them alone.
+// Before: col[w * GSD_MAX_NODES_PER_SEQ + a] = the pairs (bits of word w) whose F is node a.
+template <int NC>
+__device__ __forceinline__ void decide_in_one_wave(GraphLds &s, int n_red) {
+    constexpr int W = 2 * NC;
+    const int lane = threadIdx.x & 63;
+    const uint32_t *col = reinterpret_cast<const uint32_t *>(s.anc);
+    int r_of[NC], f_of[NC];
+    uint32_t row[NC][W];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int k = 64 * c + lane;
+        r_of[c] = k < n_red ? s.cls[k] : -1;
+        f_of[c] = k < n_red ? s.merged_to[r_of[c]] : 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) row[c][w] = 0;
+        // tree ancestors of R (R itself is nobody's first occurrence: a first occurrence is never redundant)
+        int a = k < n_red ? s.par[r_of[c]] : -1;
+        while (a >= 0) {
+#pragma unroll
+            for (int w = 0; w < W; ++w) row[c][w] |= col[w * GSD_MAX_NODES_PER_SEQ + a];
+            a = s.par[a];
+        }
+    }
+    uint64_t drawn[NC];                                     // per chunk: the pairs whose edges are drawn (uniform)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        drawn[c] = 0;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int wk = 2 * c + half;                    // the word that holds the bits of these 32 pairs
+            const int end = n_red - 64 * c < 32 * half + 32 ? n_red - 64 * c : 32 * half + 32;
+            for (int l = 32 * half; l < end; ++l) {         // uniform
+                const uint32_t bit = 1u << (l & 31);
+                const uint32_t own = __builtin_amdgcn_readlane(row[c][wk], l);
+                if (own & bit) continue;                    // R descends from F
+                uint32_t r_row[W];
+#pragma unroll
+                for (int w = wk; w < W; ++w) r_row[w] = __builtin_amdgcn_readlane(row[c][w], l);
+#pragma unroll
+                for (int c2 = c; c2 < NC; ++c2) {
+                    if (row[c2][wk] & bit) {
+#pragma unroll
+                        for (int w = wk; w < W; ++w) row[c2][w] |= r_row[w];
+                    }
+                }
+                drawn[c] |= uint64_t(1) << l;
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        if (r_of[c] >= 0) {
+            const bool edges = (drawn[c] >> lane) & 1;
+            s.flags[r_of[c]] |= edges ? kFlagMerged : 8;
+            if (edges) atomicAdd(&s.merge_cnt[f_of[c]], 1);
+        }
+    }
 }
 
 // After construct(): takes the redundant nodes in id order and decides for each whether its merge edges are drawn
-// (kFlagMerged, merge_cnt of the first occurrence) or it descends from its first occurrence (bit 3).  Leaves the
-// ancestor rows of the finished graph in s.anc.  Uses s.cls (free after construct) for the list of redundant nodes.
-__device__ void decide_merges(GraphLds &s, int n) {
+// (kFlagMerged, merge_cnt of the first occurrence) or it descends from its first occurrence (bit 3).
+// Uses s.cls (free after construct) for the list of redundant nodes and s.anc for the table of first occurrences.
+__device__ __forceinline__ void decide_merges(GraphLds &s, int n) {
     const int i = threadIdx.x;
-    const bool ex = i < n && (s.flags[i] & kFlagExists);
-    uint64_t *row = s.anc + i * 8;
+    const bool red = i < n && (s.flags[i] & kFlagExists) && (s.flags[i] & 4);
+    uint32_t *col = reinterpret_cast<uint32_t *>(s.anc);
 #pragma unroll
-    for (int w = 0; w < 8; ++w) row[w] = 0;
-    __syncthreads();
-    const int max_depth = s.max_depth;
-    for (int layer = 1; layer <= max_depth; ++layer) {      // tree ancestors: the parent's row plus the node itself
-        if (ex && s.depth[i] == layer) {
-            const int p = s.par[i];
-            if (p >= 0) {
-#pragma unroll
-                for (int w = 0; w < 8; ++w) row[w] = s.anc[p * 8 + w];
-            }
-            row[i >> 6] |= uint64_t(1) << (i & 63);
-        }
-        __syncthreads();
-    }
-    const bool red = ex && (s.flags[i] & 4);
-    const int pos = block_scan(s.scan, red ? 1 : 0) - 1;
+    for (int w = 0; w < 16; ++w) col[w * GSD_MAX_NODES_PER_SEQ + i] = 0;
+    const int pos = block_scan(s, s.scan, red ? 1 : 0) - 1;
     const int n_red = s.scan[kGraphThreads - 1];
-    __syncthreads();
-    if (red) s.cls[pos] = i;
-    __syncthreads();
-    for (int k = 0; k < n_red; ++k) {                       // uniform trip count and operands
-        const int r = s.cls[k], f = s.merged_to[r];
-        const bool cyclic = (s.anc[r * 8 + (f >> 6)] >> (f & 63)) & 1;
-        if (!cyclic) {
-            // r is no descendant of f, so nobody writes r's row in this step; every other row is written by its owner
-            if (ex && i != f && ((row[f >> 6] >> (f & 63)) & 1)) {
-#pragma unroll
-                for (int w = 0; w < 8; ++w) row[w] |= s.anc[r * 8 + w];
-            }
-            if (i == r) {
-                s.flags[i] |= kFlagMerged;
-                s.merge_cnt[f] += 1;
-            }
-        } else if (i == r) {
-            s.flags[i] |= 8;
-        }
-        __syncthreads();
+    if (red) {
+        s.cls[pos] = i;
+        atomicOr(&col[(pos >> 5) * GSD_MAX_NODES_PER_SEQ + s.merged_to[i]], 1u << (pos & 31));
     }
+    __syncthreads();
+    if (i < 64 && n_red > 0) {                              // the first wave; the others wait for its verdicts
+        if (n_red <= 64) decide_in_one_wave<1>(s, n_red);
+        else if (n_red <= 128) decide_in_one_wave<2>(s, n_red);
+        else if (n_red <= 256) decide_in_one_wave<4>(s, n_red);
+        else decide_in_one_wave<8>(s, n_red);
+    }
+    __syncthreads();
+}
+
+// Rank of the calling thread by (key, thread id) among the threads with `valid`; key in [0, GSD_MAX_NODES_PER_SEQ).
+// A wave counts its threads per key with ballots (a thread's place among its wave's equals comes out of the same
+// ballot), the counts go into table[key][wave], and a scan over the table in that order turns them into the first
+// rank of every (key, wave).  Afterwards table[key * 8] is the number of valid threads with a smaller key, and
+// `total` the number of valid threads.  `table`: 8 * GSD_MAX_NODES_PER_SEQ words.
+__device__ __forceinline__ int stable_rank(GraphLds &s, int32_t *table, int key, bool valid, int &total) {
+    constexpr int kWaves = kGraphThreads / 64;
+    const int i = threadIdx.x, lane = i & 63, wave = i >> 6;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) table[i * kWaves + w] = 0;
+    __syncthreads();
+    int place = 0;
+    uint64_t todo = __ballot(valid);
+    while (todo != 0) {                                     // one turn per distinct key of the wave
+        const int leader = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+        const int k = __builtin_amdgcn_readlane(key, leader);
+        const uint64_t same = __ballot(valid && key == k);
+        if (valid && key == k) place = __popcll(same & ((uint64_t(1) << lane) - 1));
+        if (lane == leader) table[k * kWaves + wave] = __popcll(same);
+        todo &= ~same;
+    }
+    __syncthreads();
+    int cnt[kWaves], mine = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        cnt[w] = table[i * kWaves + w];
+        mine += cnt[w];
+    }
+    int first = block_scan(s, s.scan, mine) - mine;         // threads with a smaller key
+    total = s.scan[kGraphThreads - 1];
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        table[i * kWaves + w] = first;
+        first += cnt[w];
+    }
+    __syncthreads();
+    return valid ? table[key * kWaves + wave] + place : -1;     // (the caller meets at a barrier before the table is used again)
 }
 
 __global__ __launch_bounds__(kGraphThreads) void graph_count_kernel(
@@ -244,10 +347,10 @@ __global__ __launch_bounds__(kGraphThreads) void graph_count_kernel(
     decide_merges(s, n);
     const int i = threadIdx.x;
     const bool ex = i < n && (s.flags[i] & kFlagExists);
-    const int nodes = block_scan(s.scan, ex ? 1 : 0);
+    const int nodes = block_scan(s, s.scan, ex ? 1 : 0);
     const int total_nodes = s.scan[kGraphThreads - 1];
     __syncthreads();
-    const int edges = block_scan(s.scan, ex ? 1 + (s.par[i] >= 0 ? s.merge_cnt[s.par[i]] : 0) : 0);
+    const int edges = block_scan(s, s.scan, ex ? 1 + (s.par[i] >= 0 ? s.merge_cnt[s.par[i]] : 0) : 0);
     const int total_edges = s.scan[kGraphThreads - 1];
     (void)nodes;
     (void)edges;
@@ -326,31 +429,21 @@ __global__ __launch_bounds__(kGraphThreads) void graph_fill_kernel(
         if (!__syncthreads_or(changed)) break;
     }
     // new id = rank by (level, id) among the existing nodes
-    int my_new = -1;
-    if (ex) {
-        my_new = 0;
-        const int li = level[i];
-        for (int j = 0; j < n; ++j) {
-            const int lj = level[j];
-            my_new += (lj >= 0 && (lj < li || (lj == li && j < i))) ? 1 : 0;
-        }
-    }
+    int32_t *table = reinterpret_cast<int32_t *>(s.anc);            // the ancestor rows are not needed any more
+    int32_t *node_of = table + 8 * GSD_MAX_NODES_PER_SEQ;           // node with a given new id
+    int total_nodes = 0;
+    const int my_new = stable_rank(s, table, ex ? level[i] : 0, ex, total_nodes);
     new_id[i] = my_new;
-    (void)block_scan(s.scan, ex ? 1 : 0);
-    const int total_nodes = s.scan[kGraphThreads - 1];
+    if (ex) node_of[my_new] = i;
     __syncthreads();
-    // the mergers of every first occurrence, sorted by new id
-    const int cnt_i = i < n ? s.merge_cnt[i] : 0;
-    const int off_end = block_scan(s.scan, cnt_i);
-    __syncthreads();
-    list_off[i] = off_end - cnt_i;
-    __syncthreads();
-    if (merger) {
-        int before = 0;
-        for (int j = 0; j < n; ++j)
-            before += ((s.flags[j] & kFlagMerged) && s.merged_to[j] == my_first && new_id[j] < my_new) ? 1 : 0;
-        list[list_off[my_first] + before] = my_new;
-    }
+    // the mergers of every first occurrence, sorted by new id: with the threads standing in the order of the new ids,
+    // a merger's place in the list of all mergers is its rank by (first occurrence, new id)
+    const int node_r = i < total_nodes ? node_of[i] : -1;         // this thread stands for the node with new id i
+    const bool v_merger = node_r >= 0 && (s.flags[node_r] & kFlagMerged);
+    int total_mergers = 0;
+    const int place = stable_rank(s, table, v_merger ? s.merged_to[node_r] : 0, v_merger, total_mergers);
+    list_off[i] = table[i * (kGraphThreads / 64)];
+    if (v_merger) list[place] = i;
     __syncthreads();
     // edges, in the order of the new ids
     const int my_edges = ex ? 1 + (my_par >= 0 ? s.merge_cnt[my_par] : 0) : 0;
@@ -359,7 +452,7 @@ __global__ __launch_bounds__(kGraphThreads) void graph_fill_kernel(
     __syncthreads();
     if (ex) by_rank[my_new] = my_edges;
     __syncthreads();
-    (void)block_scan(s.scan, by_rank[i]);
+    (void)block_scan(s, s.scan, by_rank[i]);
     const int total_edges = s.scan[kGraphThreads - 1];
     if (ex) {
         const int g = node_base + my_new;

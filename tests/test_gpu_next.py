@@ -468,6 +468,26 @@ def test_build_token_graph_random_trees(gpu, seed):
           f"{int(((r[4] & 4) != 0).sum())} redundant, {int(((r[4] & 8) != 0).sum())} of them cyclic", flush=True)
 
 
+@pytest.mark.parametrize("k,vocab,tau,seed,at_least", [(8, 3, 2, 5, 33), (6, 4, 3, 8, 65), (12, 4, 2, 3, 129),
+                                                       (10, 6, 3, 9, 129), (16, 6, 2, 1, 257), (30, 8, 2, 4, 257)])
+def test_build_token_graph_many_redundant_nodes(gpu, k, vocab, tau, seed, at_least):
+    """Wide trees over tiny alphabets: one sequence with more than 32, 64, 128 and 256 redundant nodes (the merge
+    decisions are taken in groups of 64), refused (cyclic) merges among them, next to a small and an empty-ish one."""
+    from test_oracle_next import random_token_tree
+    rng = np.random.default_rng(seed)
+    p, t, q = random_token_tree(rng, 512, k, vocab)
+    p2, t2, q2 = random_token_tree(rng, 37, 3, vocab)
+    node_offsets = np.array([0, len(p), len(p) + len(p2), len(p) + len(p2) + 1], dtype=np.int32)
+    par = np.concatenate([p, p2, [-1]]).astype(np.int32)
+    # token ids at the ends of the int32 range: a token is only ever compared for equality
+    ids = np.array([-1, -2**31, 2**31 - 1, 0, 1, -2, 65536, 12345678], dtype=np.int64)
+    tok = ids[np.concatenate([t, t2, [0]]).astype(np.int64)].astype(np.int32)
+    prob = np.concatenate([q, q2, [1.0]]).astype(np.float32)
+    r = compare_graph_with_oracle(gpu, node_offsets, par, tok, prob, tau, 0.0, 0.0)
+    first = r[4][:int(r[0][1])]
+    assert int(((first & 4) != 0).sum()) >= at_least, int(((first & 4) != 0).sum())
+
+
 def test_build_token_graph_flags_bad_input_and_small_capacity(gpu):
     import paper_2407_16207_amd as gsd
     par = np.array([-1, 0, 3, 0, -5, 1], dtype=np.int32)          # node 2 points forward, node 4 below -1
