@@ -13,6 +13,7 @@
 //                           max(p - q, 0) at the end of the accepted path (from p if that node has no children or the
 //                           residual is empty).  Every thread owns a contiguous slice of the vocabulary, slice sums
 //                           are scanned in thread order, the owning thread walks its slice: one fixed summation order.
+//                           (resample_held_kernel: the same with the slices kept in registers, where they fit.)
 #include "gsd_internal.h"
 
 namespace gsd {
@@ -37,12 +38,15 @@ __device__ __forceinline__ void merge_state(float &m, float &s, float m2, float 
 template <int THREADS, bool BF16>
 __global__ __launch_bounds__(THREADS) void softmax_stats_kernel(int32_t vocab, const void *__restrict__ logits,
                                                                 int64_t row_stride, float *__restrict__ row_max,
-                                                                float *__restrict__ row_sumexp) {
+                                                                float *__restrict__ row_sumexp, int64_t rows_first,
+                                                                const void *__restrict__ logits_after) {
     constexpr int ELT = BF16 ? 2 : 4;
     constexpr int PER_VEC = 16 / ELT;
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-    const int64_t row = blockIdx.x;
-    const char *row_ptr = reinterpret_cast<const char *>(logits) + row * row_stride * ELT;
+    const int64_t row = blockIdx.x;                      // rows beyond the first buffer's come from the second
+    const char *row_ptr = row < rows_first
+                              ? reinterpret_cast<const char *>(logits) + row * row_stride * ELT
+                              : reinterpret_cast<const char *>(logits_after) + (row - rows_first) * row_stride * ELT;
     float m = -__builtin_inff(), s = 0.f;
     // a batch of values joins the running state with one rescale: max of the batch first, then its exponentials
     auto add_batch = [&](const float *x, int cnt) {
@@ -120,13 +124,15 @@ __global__ __launch_bounds__(THREADS) void softmax_stats_kernel(int32_t vocab, c
 }
 
 hipError_t launch_softmax_stats(int64_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
-                                float *row_max, float *row_sumexp, hipStream_t stream) {
+                                float *row_max, float *row_sumexp, hipStream_t stream, int64_t rows_after,
+                                const void *logits_after) {
+    const dim3 grid((unsigned)(rows + rows_after));
     if (dtype == GSD_BF16)
-        hipLaunchKernelGGL((softmax_stats_kernel<256, true>), dim3((unsigned)rows), dim3(256), 0, stream, vocab, logits,
-                           row_stride, row_max, row_sumexp);
+        hipLaunchKernelGGL((softmax_stats_kernel<256, true>), grid, dim3(256), 0, stream, vocab, logits, row_stride,
+                           row_max, row_sumexp, rows, logits_after);
     else
-        hipLaunchKernelGGL((softmax_stats_kernel<256, false>), dim3((unsigned)rows), dim3(256), 0, stream, vocab, logits,
-                           row_stride, row_max, row_sumexp);
+        hipLaunchKernelGGL((softmax_stats_kernel<256, false>), grid, dim3(256), 0, stream, vocab, logits, row_stride,
+                           row_max, row_sumexp, rows, logits_after);
     return hipGetLastError();
 }
 
@@ -433,17 +439,187 @@ __global__ __launch_bounds__(kResampleThreads) void resample_kernel(const gsd_st
     if (threadIdx.x == 0) d.bonus_token[b] = pick_s;
 }
 
+// The same draw for rows whose per-thread slice fits registers (the launcher checks: the slice is a whole number of
+// 16-byte runs, at most kHeld values, rows start on 16-byte boundaries, the vocabulary ends on one): a thread fetches
+// its slice of both rows once, all loads in flight together, and every later step works from those registers: the
+// draft row's normaliser, the slice's weight sum, and (for the one thread that owns the target) the walk.  Scans go
+// through wave shuffles and one LDS hop instead of a log-step LDS scan; the order of every sum is fixed.
+constexpr int kHeld = 32;
+
+template <bool BF16>
+__global__ __launch_bounds__(kResampleThreads) void resample_held_kernel(const gsd_stochastic_desc d) {
+    constexpr int ELT = BF16 ? 2 : 4;
+    constexpr int PER_VEC = 16 / ELT;
+    constexpr int KV = kHeld / PER_VEC;
+    constexpr int kWaves = kResampleThreads / 64;
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    __shared__ float red_m[kWaves], red_s[kWaves], wave_sum[2][kWaves];
+    __shared__ int pick_s;
+
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int b = blockIdx.x;
+    const int64_t base = d.node_offsets[b];
+    int n = d.node_offsets[b + 1] - d.node_offsets[b];
+    if (n > d.max_nodes) n = d.max_nodes;
+    if (n < 0) n = 0;
+    const int end = d.end_node[b];
+    const int V = d.vocab;
+    if (t == 0) pick_s = -1;
+
+    const int64_t row_off = (end < 0 ? int64_t(b) : base + end) * d.row_stride;
+    const char *p_ptr = reinterpret_cast<const char *>(end < 0 ? d.root_logits : d.logits) + row_off * ELT;
+    const char *q_ptr = reinterpret_cast<const char *>(end < 0 ? d.root_draft_logits : d.draft_logits) + row_off * ELT;
+    const int per = (V + kResampleThreads - 1) / kResampleThreads;
+    const int x0 = t * per;
+    const int nvec = x0 < V ? min(per, V - x0) / PER_VEC : 0;     // whole 16-byte runs: the vocabulary ends on one
+    u32x4 raw_p[KV], raw_q[KV];
+#pragma unroll
+    for (int j = 0; j < KV; ++j) {                                // a run this thread does not have reads the row's first
+        const int64_t off = (j < nvec ? int64_t(x0) + j * PER_VEC : 0) * ELT;
+        raw_q[j] = *reinterpret_cast<const u32x4 *>(q_ptr + off);
+        raw_p[j] = *reinterpret_cast<const u32x4 *>(p_ptr + off);
+    }
+    const float p_max = end < 0 ? d.row_max[d.total_nodes + b] : d.row_max[base + end];
+    const float p_sum = end < 0 ? d.row_sumexp[d.total_nodes + b] : d.row_sumexp[base + end];
+    // does the end node (or the root) have children ?
+    const int32_t e0 = d.parent_offsets[base], e1 = d.parent_offsets[base + n];
+    int mine = 0;
+    for (int e = e0 + t; e < e1; e += kResampleThreads) mine |= (d.parent_idx[e] == end);
+
+    auto value = [&](const u32x4 v, int e) -> float {
+        if (BF16) return (e & 1) ? __uint_as_float(v[e >> 1] & 0xffff0000u) : __uint_as_float(v[e >> 1] << 16);
+        return __uint_as_float(v[e]);
+    };
+    // the draft row's own (max, sum)
+    float m = -__builtin_inff(), sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < KV; ++j)
+        if (j < nvec) {
+#pragma unroll
+            for (int e = 0; e < PER_VEC; ++e) m = fmaxf(m, value(raw_q[j], e));
+        }
+    if (m > -__builtin_inff()) {
+#pragma unroll
+        for (int j = 0; j < KV; ++j)
+            if (j < nvec) {
+#pragma unroll
+                for (int e = 0; e < PER_VEC; ++e) sum += __expf(value(raw_q[j], e) - m);
+            }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const float m2 = __shfl_xor(m, off, 64), s2 = __shfl_xor(sum, off, 64);
+        merge_state(m, sum, m2, s2);
+    }
+    if (lane == 0) {
+        red_m[wave] = m;
+        red_s[wave] = sum;
+    }
+    const bool use_residual = __syncthreads_or(mine) != 0;
+    float q_max = red_m[0], q_sum = red_s[0];
+    for (int w = 1; w < kWaves; ++w) merge_state(q_max, q_sum, red_m[w], red_s[w]);
+
+    auto weight_of = [&](float lp, float lq, bool residual) -> float {
+        const float pp = __expf(lp - p_max) / p_sum;
+        return residual ? fmaxf(pp - __expf(lq - q_max) / q_sum, 0.f) : pp;
+    };
+    // the cumulative weight before this thread's slice and up to its end: the slice in ascending token order, the
+    // wave in lane order, the waves in their order
+    float before = 0.f, upto = 0.f, total = 0.f;
+    auto scan = [&](bool residual, int turn) {
+        float local = 0.f;
+#pragma unroll
+        for (int j = 0; j < KV; ++j)
+            if (j < nvec) {
+#pragma unroll
+                for (int e = 0; e < PER_VEC; ++e) local += weight_of(value(raw_p[j], e), value(raw_q[j], e), residual);
+            }
+        float incl = local;
+#pragma unroll
+        for (int dd = 1; dd < 64; dd <<= 1) {
+            const float up = __shfl_up(incl, dd, 64);
+            if (lane >= dd) incl += up;
+        }
+        const float left = __shfl_up(incl, 1, 64);
+        if (lane == 63) wave_sum[turn][wave] = incl;
+        __syncthreads();
+        float run = 0.f, mine_base = 0.f;
+        for (int w = 0; w < kWaves; ++w) {
+            if (w == wave) mine_base = run;
+            run += wave_sum[turn][w];
+        }
+        total = run;
+        before = lane == 0 ? mine_base : mine_base + left;
+        upto = mine_base + incl;
+    };
+    bool residual = use_residual;
+    scan(residual, 0);
+    if (residual && !(total > 0.f)) {                        // empty residual: draw from p
+        residual = false;
+        scan(false, 1);
+    }
+    const float target = d.resample_u[b] * total;
+    // the owner of the target walks its slice; the smallest token whose cumulative weight exceeds the target
+    if (before <= target && target < upto) {
+        float run = before;
+        int pick = -1, last = -1;
+#pragma unroll
+        for (int j = 0; j < KV; ++j)
+            if (j < nvec) {
+#pragma unroll
+                for (int e = 0; e < PER_VEC; ++e) {
+                    const float w = weight_of(value(raw_p[j], e), value(raw_q[j], e), residual);
+                    run += w;
+                    if (w > 0.f) last = x0 + j * PER_VEC + e;
+                    if (pick < 0 && run > target) pick = x0 + j * PER_VEC + e;
+                }
+            }
+        pick_s = pick >= 0 ? pick : last;                   // rounding inside the slice: its last token with weight
+    }
+    __syncthreads();
+    if (pick_s < 0) {                                       // target == total by rounding: the last token with weight
+        int last = -1;
+#pragma unroll
+        for (int j = 0; j < KV; ++j)
+            if (j < nvec) {
+#pragma unroll
+                for (int e = 0; e < PER_VEC; ++e)
+                    if (weight_of(value(raw_p[j], e), value(raw_q[j], e), residual) > 0.f) last = x0 + j * PER_VEC + e;
+            }
+        for (int off = 32; off > 0; off >>= 1) last = max(last, __shfl_xor(last, off, 64));
+        __shared__ int wave_last[kWaves];
+        if (lane == 0) wave_last[wave] = last;
+        __syncthreads();
+        if (t == 0) {
+            int best = 0;
+            for (int w = 0; w < kWaves; ++w) best = max(best, wave_last[w]);
+            pick_s = best;
+        }
+        __syncthreads();
+    }
+    if (t == 0) d.bonus_token[b] = pick_s;
+}
+
 hipError_t launch_accept_stochastic(const gsd_stochastic_desc &d, hipStream_t stream) {
+    // the node rows and, behind them, the root rows: one launch
     hipError_t err = launch_softmax_stats(d.total_nodes, d.vocab, d.dtype, d.logits, d.row_stride, d.row_max,
-                                          d.row_sumexp, stream);
-    if (err != hipSuccess) return err;
-    err = launch_softmax_stats(d.batch, d.vocab, d.dtype, d.root_logits, d.row_stride, d.row_max + d.total_nodes,
-                               d.row_sumexp + d.total_nodes, stream);
+                                          d.row_sumexp, stream, d.batch, d.root_logits);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(accept_stochastic_kernel, dim3(d.batch), dim3(kStochThreads), 0, stream, d);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(resample_kernel, dim3(d.batch), dim3(kResampleThreads), 0, stream, d);
+    // slices that fit registers: see resample_held_kernel
+    const int elt = d.dtype == GSD_BF16 ? 2 : 4;
+    const int per = (d.vocab + kResampleThreads - 1) / kResampleThreads;
+    auto aligned = [&](const void *ptr) { return reinterpret_cast<uintptr_t>(ptr) % 16 == 0; };
+    const bool held = per <= kHeld && (per * elt) % 16 == 0 && (int64_t(d.vocab) * elt) % 16 == 0 &&
+                      (d.row_stride * elt) % 16 == 0 && aligned(d.logits) && aligned(d.root_logits) &&
+                      aligned(d.draft_logits) && aligned(d.root_draft_logits);
+    if (held && d.dtype == GSD_BF16)
+        hipLaunchKernelGGL(resample_held_kernel<true>, dim3(d.batch), dim3(kResampleThreads), 0, stream, d);
+    else if (held)
+        hipLaunchKernelGGL(resample_held_kernel<false>, dim3(d.batch), dim3(kResampleThreads), 0, stream, d);
+    else
+        hipLaunchKernelGGL(resample_kernel, dim3(d.batch), dim3(kResampleThreads), 0, stream, d);
     return hipGetLastError();
 }
 

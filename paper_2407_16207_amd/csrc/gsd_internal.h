@@ -44,8 +44,10 @@ hipError_t launch_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers
                             const int32_t *prefix_lens, const int32_t *accept_len, const int32_t *accept_path,
                             int32_t *new_prefix_lens, hipStream_t stream);
 
+// rows_after further rows are taken from logits_after (same stride); their results follow the first buffer's
 hipError_t launch_softmax_stats(int64_t rows, int32_t vocab, int dtype, const void *logits, int64_t row_stride,
-                                float *row_max, float *row_sumexp, hipStream_t stream);
+                                float *row_max, float *row_sumexp, hipStream_t stream, int64_t rows_after = 0,
+                                const void *logits_after = nullptr);
 hipError_t launch_accept_stochastic(const gsd_stochastic_desc &d, hipStream_t stream);
 
 hipError_t launch_build_graph(int32_t batch, int32_t max_nodes, const int32_t *node_offsets, const int32_t *tree_parent,

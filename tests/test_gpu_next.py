@@ -245,7 +245,9 @@ def stochastic_problem(rng, sizes, vocab, dtype, max_parents=3, peaked=2.0):
 @pytest.mark.parametrize("dtype,vocab,sizes", [("f32", 1003, [60, 1, 200, 17, 512, 33]),
                                                ("bf16", 1003, [60, 1, 200, 17, 512, 33]),
                                                # 8192: the draw kernel's slices are whole 16-byte runs (its vector path)
-                                               ("f32", 8192, [60, 40, 150, 17, 90, 33]), ("bf16", 8192, [60, 40, 150, 17, 90, 33])])
+                                               ("f32", 8192, [60, 40, 150, 17, 90, 33]), ("bf16", 8192, [60, 40, 150, 17, 90, 33]),
+                                               # 32000: a full register slice (32 values) per thread of the draw kernel
+                                               ("f32", 32000, [30, 12, 25, 7, 40, 18, 33]), ("bf16", 32000, [30, 12, 25, 7, 40, 18, 33])])
 def test_softmax_stats_and_stochastic_acceptance(gpu, dtype, vocab, sizes):
     import paper_2407_16207_amd as gsd
     rng = np.random.default_rng((31 if dtype == "f32" else 32) + vocab)
