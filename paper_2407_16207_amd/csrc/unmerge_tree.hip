@@ -101,18 +101,25 @@ __device__ bool count_paths(int n, int64_t base, const int32_t *__restrict__ par
         __syncthreads();
         if (flags[slot] == 0) break;                      // uniform: read after the barrier
     }
-    // exclusive scan (saturating addition is associative on [0, 2^62]); first[n] = total
+    // exclusive scan (saturating addition is associative on [0, 2^62]); first[n] = total.  Within a wave by shuffles,
+    // across waves through the eight wave totals.
+    __shared__ uint64_t wave_total[kUnmergeThreads / 64];
+    const int lane = i & 63, wave = i >> 6;
     uint64_t v = i < n ? cnt[i] : 0;
-    first[i + 1] = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint64_t up = __shfl_up(static_cast<unsigned long long>(v), d, 64);
+        if (lane >= d) v = sat_add(v, up);
+    }
+    if (lane == 63) wave_total[wave] = v;
+    __syncthreads();
+    uint64_t before = 0;
+#pragma unroll
+    for (int w = 0; w < kUnmergeThreads / 64; ++w)
+        if (w < wave) before = sat_add(before, wave_total[w]);
+    first[i + 1] = sat_add(before, v);
     if (i == 0) first[0] = 0;
     __syncthreads();
-    for (int d = 1; d < kUnmergeThreads; d <<= 1) {
-        const uint64_t add = i >= d ? first[i + 1 - d] : 0;
-        __syncthreads();
-        v = sat_add(v, add);
-        first[i + 1] = v;
-        __syncthreads();
-    }
     return bad;
 }
 
