@@ -518,9 +518,10 @@ __global__ __launch_bounds__(kResampleThreads) void resample_held_kernel(const g
     float q_max = red_m[0], q_sum = red_s[0];
     for (int w = 1; w < kWaves; ++w) merge_state(q_max, q_sum, red_m[w], red_s[w]);
 
+    const float p_scale = 1.f / p_sum, q_scale = 1.f / q_sum;     // one division per row instead of one per token
     auto weight_of = [&](float lp, float lq, bool residual) -> float {
-        const float pp = __expf(lp - p_max) / p_sum;
-        return residual ? fmaxf(pp - __expf(lq - q_max) / q_sum, 0.f) : pp;
+        const float pp = __expf(lp - p_max) * p_scale;
+        return residual ? fmaxf(pp - __expf(lq - q_max) * q_scale, 0.f) : pp;
     };
     // the cumulative weight before this thread's slice and up to its end: the slice in ascending token order, the
     // wave in lane order, the waves in their order
