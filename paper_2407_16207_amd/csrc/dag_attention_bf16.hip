@@ -26,8 +26,9 @@
 // each lane four consecutive keys of one channel from a row-major tile) are free of bank conflicts.
 //
 // Schedule.  The loop is a hand-laid software pipeline: while the matrix pipe computes the scores of tile i+1
-// the vector ALU exponentiates tile i; while the matrix pipe accumulates P.V of tile i the vector ALU reduces
-// the running max of tile i+1.  Two barriers per tile, each followed by the prefetch of the buffer just freed.
+// the vector ALU exponentiates the second half of tile i's scores; while the matrix pipe accumulates P.V of tile i
+// the vector ALU exponentiates the first half of tile i+1's.  Two barriers per tile, each followed by the prefetch
+// of the buffer just freed.
 //
 // Small problems are split along the KV axis (gsd_attn_desc.num_splits); a split writes unnormalised fp32
 // partials (O, running max, running sum) and a second kernel merges them in split order.
