@@ -281,7 +281,7 @@ __device__ __forceinline__ void decide_merges(GraphLds &s, int n) {
         atomicOr(&col[(pos >> 5) * GSD_MAX_NODES_PER_SEQ + s.merged_to[i]], 1u << (pos & 31));
     }
     __syncthreads();
-    if (i < 64 && n_red > 0) {                              // the first wave; the others wait for its verdicts
+    if (i < 64 && n_red > 0) {                              // the first wave; the others wait for its decisions
         if (n_red <= 64) decide_in_one_wave<1>(s, n_red);
         else if (n_red <= 128) decide_in_one_wave<2>(s, n_red);
         else if (n_red <= 256) decide_in_one_wave<4>(s, n_red);
