@@ -241,6 +241,7 @@ int gsd_gather_rows(int64_t rows, int64_t row_bytes, const void *src, int64_t sr
  * gsd_accept_longest_path returns (ids strictly increasing, so accept_path[b][j] >= j); an id outside
  * [j, max_nodes) skips that row.
  *
+ *   max_nodes          1..GSD_MAX_NODES_PER_SEQ (more: GSD_ERR_UNSUPPORTED)
  *   num_layers >= 1; layer l of K starts at (char*)k + l*layer_stride_bytes (same for v)
  *   row_bytes          bytes of one token's K (or V) in one layer (all KV heads), multiple of 16
  *   token_stride_bytes distance between consecutive rows, multiple of 16, >= row_bytes

@@ -29,20 +29,24 @@ __global__ __launch_bounds__(kCommitThreads) void commit_kv_kernel(
     const int layer = blockIdx.y;
     const int col0 = blockIdx.x * kCommitThreads;
     const int cols = min(kCommitThreads, vecs_per_row - col0);          // >= 1 by the grid's construction
+    // every index this work-group needs is fetched in one round trip: the path entries do not wait for the length
+    static_assert(GSD_MAX_NODES_PER_SEQ <= 2 * kCommitThreads, "two path entries per thread cover a sequence");
+    const int32_t *path = accept_path + int64_t(b) * max_nodes;
+    const int j_a = threadIdx.x, j_b = threadIdx.x + kCommitThreads;
+    const int32_t s_a = j_a < max_nodes ? path[j_a] : -1;
+    const int32_t s_b = j_b < max_nodes ? path[j_b] : -1;
     int len = accept_len[b];
-    if (len > max_nodes) len = max_nodes;
     const int P = prefix_lens[b];
+    const int64_t seq_row0 = kv_offsets[b];
+    if (len > max_nodes) len = max_nodes;
     if (which == 0 && layer == 0 && blockIdx.x == 0 && threadIdx.x == 0) new_prefix_lens[b] = P + (len > 0 ? len : 0);
     if (len <= 0) return;                                               // uniform for the work-group
 
-    const int32_t *path = accept_path + int64_t(b) * max_nodes;
-    for (int j = threadIdx.x; j < len; j += kCommitThreads) {
-        const int s = path[j];
-        src_of[j] = (s > j && s < max_nodes) ? s : -1;                 // s == j: already in place
-    }
+    if (j_a < len) src_of[j_a] = (s_a > j_a && s_a < max_nodes) ? s_a : -1;     // s == j: already in place
+    if (j_b < len) src_of[j_b] = (s_b > j_b && s_b < max_nodes) ? s_b : -1;
     __syncthreads();
 
-    char *rows = (which ? v : k) + layer * layer_stride + (kv_offsets[b] + P) * token_stride + int64_t(col0) * 16;
+    char *rows = (which ? v : k) + layer * layer_stride + (seq_row0 + P) * token_stride + int64_t(col0) * 16;
     const int rows_per_chunk = kChunkPieces / cols;                     // >= kPieces
     for (int j0 = 0; j0 < len; j0 += rows_per_chunk) {
         const int pieces = min(rows_per_chunk, len - j0) * cols;

@@ -269,6 +269,8 @@ int gsd_commit_kv(int32_t batch, int32_t max_nodes, int32_t num_layers, int64_t 
         return fail(GSD_ERR_INVALID_ARG, "batch, max_nodes and num_layers must be >= 1");
     if (batch > 32767 || num_layers > 65535)
         return fail(GSD_ERR_UNSUPPORTED, "batch <= 32767 and num_layers <= 65535 (grid limits)");
+    if (max_nodes > GSD_MAX_NODES_PER_SEQ)
+        return fail(GSD_ERR_UNSUPPORTED, "max_nodes %d exceeds %d", max_nodes, GSD_MAX_NODES_PER_SEQ);
     if (row_bytes < 16 || row_bytes % 16 != 0 || token_stride_bytes % 16 != 0 || token_stride_bytes < row_bytes)
         return fail(GSD_ERR_INVALID_ARG, "row_bytes and token_stride_bytes must be multiples of 16, stride >= row");
     if (row_bytes / 16 > INT32_MAX) return fail(GSD_ERR_UNSUPPORTED, "row_bytes too large");

@@ -128,6 +128,7 @@ def test_unmerge_gather_commit_validate(lib):
         assert lib.gsd_gather_rows(*bad) == gsd.GSD_ERR_INVALID_ARG, pos
     good = [2, 64, 4, 2048, p, q, 2048, 1 << 20, p, p, p, p, q, null]
     for pos, value, code in ((0, 0, gsd.GSD_ERR_INVALID_ARG), (2, 0, gsd.GSD_ERR_INVALID_ARG),
+                             (1, 513, gsd.GSD_ERR_UNSUPPORTED),
                              (2, 70000, gsd.GSD_ERR_UNSUPPORTED), (3, 2040, gsd.GSD_ERR_INVALID_ARG),
                              (6, 1024, gsd.GSD_ERR_INVALID_ARG), (7, 1000, gsd.GSD_ERR_INVALID_ARG),
                              (4, ctypes.c_void_p(0x10008), gsd.GSD_ERR_INVALID_ARG), (12, p, gsd.GSD_ERR_INVALID_ARG),
