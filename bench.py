@@ -562,23 +562,15 @@ def main():
     # cost 13 us per step here (0.293 ms without, 0.306 ms with four), so the per-stage times and the attention kernel's
     # launch duration come from a further, single-stream pass of K steps that carries them.  With --streams 2 both schedules
     # are timed and the headline is the two-stream one; --streams 1 runs the one-stream schedule only.
-    one_ms, one_ms_events = timed_pass(step)
-    two_ms, two_ms_events = timed_pass(step_two_streams) if args.streams == 2 else (None, None)   # --streams 1: never run
-    ms_per_step, ms_per_step_events = (two_ms, two_ms_events) if args.streams == 2 else (one_ms, one_ms_events)
+    # Order of the passes: a chip that has idled (here: while the inputs were generated and uploaded) raises its clocks
+    # over roughly its first hundred steps of work (0.345 ms for the first ten steps after half a second of idling,
+    # 0.305 for steps 21-30, 0.291 from about step 110 on), so the passes whose figures are secondary run first and
+    # the headline pass last: cold-cache pass, then (two streams only) the one-stream pass, then the pass with the
+    # events, then the headline pass.  Each pass still does its own W warm-up steps and times exactly K steps.
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(ev[s])
-    torch.cuda.synchronize()
-    ms_per_step_staged = (time.perf_counter() - t0) * 1e3 / args.steps
-    stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])      # ms
-    mask_ms, attn_ms, accept_ms = stage.mean(axis=0)
-
-    # the same step with every input tensor rotated over three copies, so that nothing a step reads can still be
-    # in the 256 MB last-level cache from the step before ("cold"; the default loop above re-reads the same
-    # buffers, of which at most 256 MB can have stayed cached)
+    # the step with every input tensor rotated over three copies, so that nothing a step reads can still be in the
+    # 256 MB last-level cache from the step before ("cold"; the other passes re-read the same buffers, of which at
+    # most 256 MB can have stayed cached).  First of the passes, see above: its first steps also meet an idle chip.
     copies = [(q, k, v, logits, desc)]
     for _ in range(2):
         q2, k2, v2, l2 = q.clone(), k.clone(), v.clone(), logits.clone()
@@ -601,18 +593,38 @@ def main():
     cold_n = max(6, min(60, args.steps))
     for i in range(3):
         cold_step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(cold_n):
-        cold_step(i)
-    torch.cuda.synchronize()
-    cold_ms = (time.perf_counter() - t0) * 1e3 / cold_n
     cev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(cold_n)]
     for i in range(cold_n):
         cold_step(i, cev[i])
     torch.cuda.synchronize()
     cold_attn_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in cev]))
+    t0 = time.perf_counter()
+    for i in range(cold_n):
+        cold_step(i)
+    torch.cuda.synchronize()
+    cold_ms = (time.perf_counter() - t0) * 1e3 / cold_n
     del copies
+
+    one_ms = one_ms_events = two_ms = two_ms_events = None
+    if args.streams == 2:
+        one_ms, one_ms_events = timed_pass(step)
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    ms_per_step_staged = (time.perf_counter() - t0) * 1e3 / args.steps
+    stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])      # ms
+    mask_ms, attn_ms, accept_ms = stage.mean(axis=0)
+
+    if args.streams == 2:
+        two_ms, two_ms_events = timed_pass(step_two_streams)
+        ms_per_step, ms_per_step_events = two_ms, two_ms_events
+    else:                                                                      # --streams 1: the two-stream step never runs
+        one_ms, one_ms_events = timed_pass(step)
+        ms_per_step, ms_per_step_events = one_ms, one_ms_events
 
     # argmax alone (the HBM-bound part of the acceptance call), on the same stream
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -673,10 +685,15 @@ def main():
         "ms_per_step_by_hip_events": ms_per_step_events,
         "schedule": {"streams": args.streams, "ms_per_step_one_stream": one_ms, "ms_per_step_two_streams": two_ms,
                      "note": "two streams: mask + attention on one, argmax + acceptance on the other (same priority), "
-                             "forked and joined inside every step"},
+                             "forked and joined inside every step",
+                     "pass_order": (["cold_cache", "one_stream", "stage_ms", "two_streams (headline)"]
+                                    if args.streams == 2 else ["cold_cache", "stage_ms", "one_stream (headline)"]),
+                     "pass_order_note": "every pass does its own W warm-up steps and times exactly K steps; the headline "
+                                        "pass runs last because a chip that has idled raises its clocks over its "
+                                        "first ~100 steps of work"},
         "stage_ms": {"mask": float(mask_ms), "attention": float(attn_ms), "argmax_plus_accept": float(accept_ms),
                      "argmax_alone": float(argmax_ms), "ms_per_step_of_this_pass": ms_per_step_staged,
-                     "note": "second pass of the same K steps with a HIP event between the launches (the events "
+                     "note": "a pass of the same K steps with a HIP event between the launches (the events "
                              "themselves lengthen a step; the headline pass carries none)"},
         "cold_cache": {"steps": cold_n, "ms_per_step": cold_ms, "value": T / (cold_ms * 1e-3),
                        "attention_ms": cold_attn_ms, "note": "inputs rotated over 3 copies (> 256 MB apart)"},
