@@ -490,6 +490,15 @@ def test_build_token_graph_many_redundant_nodes(gpu, k, vocab, tau, seed, at_lea
     assert int(((first & 4) != 0).sum()) >= at_least, int(((first & 4) != 0).sum())
 
 
+def test_build_token_graph_many_sequences(gpu):
+    """More sequences than a work-group has threads: every work-group adds up the counts of all sequences before it."""
+    rng = np.random.default_rng(99)
+    sizes = [int(x) for x in rng.integers(1, 40, 700)] + [512, 300]
+    node_offsets, par, tok, q = token_trees(rng, sizes, 3, 5)
+    r = compare_graph_with_oracle(gpu, node_offsets, par, tok, q, 2, 0.0, 0.0)
+    assert len(r[0]) == len(sizes) + 1 and int(((r[4] & 4) != 0).sum()) > 1000
+
+
 def test_build_token_graph_flags_bad_input_and_small_capacity(gpu):
     import paper_2407_16207_amd as gsd
     par = np.array([-1, 0, 3, 0, -5, 1], dtype=np.int32)          # node 2 points forward, node 4 below -1
