@@ -344,6 +344,33 @@ def test_stochastic_limits_on_gpu(gpu, ref):
     assert np.array_equal(ln.cpu().numpy(), dl) and np.array_equal(path.cpu().numpy(), dpath) and (dl > 0).any()
 
 
+def test_many_sequences_unmerge_mask_and_acceptance(gpu, ref):
+    """650 small graphs in one call: more sequences than a work-group has threads (the packed position of a
+    sequence's tree is a sum over all sequences before it), one work-group per sequence everywhere else."""
+    import paper_2407_16207_amd as gsd
+    from paper_2407_16207_amd.workload import random_dag, merged_tree_dag
+    rng = np.random.default_rng(123)
+    dags = [(merged_tree_dag(rng, int(n), 3, int(rng.integers(0, 4))) if rng.random() < 0.5
+             else random_dag(rng, int(n), 3, 0.2)) for n in rng.integers(1, 30, 650)]
+    no, poff, pidx = pack(dags)
+    o, tpar, tpo, to, cnt, fl = run_unmerge(gpu, gsd, no, poff, pidx, 32, 64)
+    ro, rtp, rto, rcnt = gsd_next.unmerge_to_tree(no, poff, pidx, 64)
+    assert fl == 0 and np.array_equal(o, ro) and np.array_equal(cnt, rcnt)
+    assert np.array_equal(tpar, rtp) and np.array_equal(to, rto)
+    n_max = int(np.diff(no).max())
+    mask = gsd.gsd_build_mask(gpu.to_dev(no), gpu.to_dev(poff), gpu.to_dev(pidx), n_max)
+    rmask, _ = ref.build_mask(no, poff, pidx)
+    assert np.array_equal(gpu.mask_to_numpy(mask), rmask)
+    T, B = int(no[-1]), len(no) - 1
+    tokens, pred = rng.integers(0, 3, T).astype(np.int32), rng.integers(0, 3, T).astype(np.int32)
+    rootp = rng.integers(0, 3, B).astype(np.int32)
+    ln, path, bonus, _ = gsd.gsd_accept_longest_path(gpu.to_dev(no), gpu.to_dev(poff), gpu.to_dev(pidx),
+                                                     gpu.to_dev(tokens), gpu.to_dev(rootp), n_max, pred=gpu.to_dev(pred))
+    wl, wp, wb = ref.accept_longest_path(no, poff, pidx, tokens, pred, rootp)
+    assert np.array_equal(ln.cpu().numpy(), wl) and np.array_equal(path.cpu().numpy(), wp)
+    assert np.array_equal(bonus.cpu().numpy(), wb) and (wl > 0).sum() > 100
+
+
 # -------------------------------------------------------------------------------------- graph construction
 def token_trees(rng, sizes, k, vocab):
     from test_oracle_next import random_token_tree
