@@ -431,9 +431,11 @@ def main():
     ap.add_argument("--cpu-sample-nodes", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next", action="store_true", help="skip the un-merge and KV-commit measurements")
-    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
-                    help="2 (default): the argmax + acceptance call runs on a second stream of the same priority next to "
-                         "mask + attention, forked at the start of every step and joined at its end; 1: all on one stream")
+    ap.add_argument("--streams", type=int, default=0, choices=[0, 1, 2],
+                    help="2: the argmax + acceptance call runs on a second stream of the same priority next to mask + "
+                         "attention, forked at the start of every step and joined at its end; 1: all on one stream; "
+                         "0 (default): 2 for configs 4 and 5, 1 for the small configs, whose steps are shorter than "
+                         "what the fork and the join cost")
     ap.add_argument("--no-config5", action="store_true", help="skip the config-5 graph-against-tree attention leg")
     ap.add_argument("--cache-layers", type=int, default=80, help="depth of the KV cache the commit step is timed on")
     ap.add_argument("--splits", type=int, default=0, help="force the attention KV split count (0 = library's choice)")
@@ -444,6 +446,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+    if args.streams == 0:
+        args.streams = 2 if args.config >= 4 else 1
 
     import numpy as np
     import torch
