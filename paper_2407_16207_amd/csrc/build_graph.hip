@@ -46,7 +46,7 @@ struct GraphLds {
     int32_t merge_cnt[GSD_MAX_NODES_PER_SEQ];  // nodes merged into this one (merge edges actually drawn)
     // 32 KB used three times over: the key table of the tau-gram classes, then (merge decisions) per node the set of
     // redundant nodes it is the first occurrence for, word-major, then the counting tables of the renumbering
-    uint64_t anc[GSD_MAX_NODES_PER_SEQ * 8];
+    uint64_t pool[GSD_MAX_NODES_PER_SEQ * 8];
     int32_t wave_tot[16];
     int32_t bad;
     int32_t max_depth;
@@ -55,7 +55,7 @@ constexpr int kFlagExists = 0x100;             // internal flag bits, above the 
 constexpr int kFlagMerged = 0x200;             // redundant node whose merge edges are drawn
 
 // Runs the construction for the calling work-group's sequence; afterwards flags (bit8 = exists), merged_to and depth
-// are final.  Returns the node count through n_out.
+// are final.
 __device__ __forceinline__ void construct(GraphLds &s, int n, int64_t base, const int32_t *__restrict__ tree_parent,
                           const int32_t *__restrict__ tokens, const float *__restrict__ draft_prob, int tau,
                           float theta_prob, float theta_sib) {
@@ -112,8 +112,8 @@ __device__ __forceinline__ void construct(GraphLds &s, int n, int64_t base, cons
     // slot always turns up) and leave the minimum of their ids there.
     constexpr int kSlots = 2048;
     constexpr unsigned long long kEmpty = ~0ull;       // no key looks like this: the low half is a class + 1 <= 512
-    unsigned long long *slot_key = reinterpret_cast<unsigned long long *>(s.anc);
-    int32_t *slot_min = reinterpret_cast<int32_t *>(s.anc + kSlots);
+    unsigned long long *slot_key = reinterpret_cast<unsigned long long *>(s.pool);
+    int32_t *slot_min = reinterpret_cast<int32_t *>(s.pool + kSlots);
     int my_cls = -1;                                   // class at the level just finished (level 0: everyone alike)
     const int32_t my_tok = i < n ? s.tok[i] : 0;
     const int my_par = i < n ? s.par[i] : -2;
@@ -211,7 +211,7 @@ template <int NC>
 __device__ __forceinline__ void decide_in_one_wave(GraphLds &s, int n_red) {
     constexpr int W = 2 * NC;
     const int lane = threadIdx.x & 63;
-    const uint32_t *col = reinterpret_cast<const uint32_t *>(s.anc);
+    const uint32_t *col = reinterpret_cast<const uint32_t *>(s.pool);
     int r_of[NC], f_of[NC];
     uint32_t row[NC][W];
 #pragma unroll
@@ -267,11 +267,11 @@ __device__ __forceinline__ void decide_in_one_wave(GraphLds &s, int n_red) {
 
 // After construct(): takes the redundant nodes in id order and decides for each whether its merge edges are drawn
 // (kFlagMerged, merge_cnt of the first occurrence) or it descends from its first occurrence (bit 3).
-// Uses s.cls (free after construct) for the list of redundant nodes and s.anc for the table of first occurrences.
+// Uses s.cls (free after construct) for the list of redundant nodes and s.pool for the table of first occurrences.
 __device__ __forceinline__ void decide_merges(GraphLds &s, int n) {
     const int i = threadIdx.x;
     const bool red = i < n && (s.flags[i] & kFlagExists) && (s.flags[i] & 4);
-    uint32_t *col = reinterpret_cast<uint32_t *>(s.anc);
+    uint32_t *col = reinterpret_cast<uint32_t *>(s.pool);
 #pragma unroll
     for (int w = 0; w < 16; ++w) col[w * GSD_MAX_NODES_PER_SEQ + i] = 0;
     const int pos = block_scan(s, s.scan, red ? 1 : 0) - 1;
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(kGraphThreads) void graph_fill_kernel(
         if (!__syncthreads_or(changed)) break;
     }
     // new id = rank by (level, id) among the existing nodes
-    int32_t *table = reinterpret_cast<int32_t *>(s.anc);            // the ancestor rows are not needed any more
+    int32_t *table = reinterpret_cast<int32_t *>(s.pool);            // the ancestor rows are not needed any more
     int32_t *node_of = table + 8 * GSD_MAX_NODES_PER_SEQ;           // node with a given new id
     int total_nodes = 0;
     const int my_new = stable_rank(s, table, ex ? level[i] : 0, ex, total_nodes);
